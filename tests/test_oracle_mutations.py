@@ -1,0 +1,107 @@
+"""Are the pins sharp?  Each case plants one plausible mistake in a copy of the
+oracle's C source (on the CPU), compiles it, and checks that the pin battery of
+test_oracle_pins.py fails for it.  The unmodified source must pass the battery."""
+import os
+import subprocess
+
+import pytest
+
+from oracle import pier_oracle as O
+import test_oracle_pins as pins
+
+SRC = open(os.path.join(os.path.dirname(O.__file__), "pier_oracle.c")).read()
+
+# (name, text in the oracle, mistaken replacement)
+MUTATIONS = [
+    ("drop weight decay", "+ wd * (*p);", ";"),
+    ("decay with the wrong sign", "+ wd * (*p);", "- wd * (*p);"),
+    ("ascent instead of descent", "*p = *p - lr * u;", "*p = *p + lr * u;"),
+    ("eps inside the root", "mh / (sqrtf(vh) + eps)", "mh / sqrtf(vh + eps)"),
+    ("no bias correction of m", "float mh = mn / bc1;", "float mh = mn;"),
+    ("no bias correction of v", "float vh = vn / bc2;", "float vh = vn;"),
+    ("bias correction one step late", "pow((double)beta1, (double)step)", "pow((double)beta1, (double)(step - 1) + 1e-9)"),
+    ("betas swapped in the moments", "float mn = beta1 * (*m) + om1 * g;", "float mn = beta2 * (*m) + om2 * g;"),
+    ("first moment of g squared", "om1 * g;", "om1 * g * g;"),
+    ("second moment of g, not g^2", "(om2 * g) * g;", "(om2 * g);"),
+    ("moments not stored", "*m = mn;", ""),
+    ("decay uses updated theta", "float u = mh / (sqrtf(vh) + eps) + wd * (*p);\n    *p = *p - lr * u;",
+     "*p = *p - lr * (mh / (sqrtf(vh) + eps));\n    *p = *p - lr * wd * (*p) * 40.0f;"),
+    ("bf16 shifted wrong", "(uint32_t)g[i] << 16", "(uint32_t)g[i] << 15"),
+    ("grad_scale ignored", "if (grad_scale != 1.0f) g = g * grad_scale;", ""),
+    ("sum instead of mean", "float d = s * invG;", "float d = s;"),
+    ("anchor minus model", "s = s + (theta[g][i] - a[i]);", "s = s + (a[i] - theta[g][i]);"),
+    ("first group only", "for (int g = 0; g < G; ++g) s = s + (theta[g][i] - a[i]);",
+     "for (int g = 0; g < 1; ++g) s = s + (theta[g][i] - a[i]) * (float)G;"),
+    ("momentum without mu", "float Mn = mu * M[i] + d;", "float Mn = M[i] + d;"),
+    ("heavy ball, no Nesterov term", "lr * (mu * Mn + d)", "lr * Mn"),
+    ("look-ahead uses the old momentum",
+     "M[i] = Mn;\n        if (phase == 1) {\n            float x = a[i] + lr * (mu * Mn + d);",
+     "float Mold = M[i]; M[i] = Mn;\n        if (phase == 1) {\n            float x = a[i] + lr * (mu * Mold + d);"),
+    ("lr on the gradient only", "a[i] + lr * (mu * Mn + d)", "a[i] + (mu * Mn + lr * d)"),
+    ("momentum not stored", "M[i] = Mn;", ""),
+    ("groups not re-synchronised", "for (int g = 0; g < G; ++g) theta[g][i] = x;", "theta[0][i] = x;"),
+    ("anchor not advanced", "a[i] = x;", ""),
+    ("warmup applies the step", "if (phase == 1) {", "if (phase == 1 || phase == 0) {"),
+    ("warmup keeps the old anchor", "a[i] = s2 * invG;", ""),
+    ("mu bands swapped", "return 0.99f;", "return 0.95f;"),
+    ("mu boundary at 15% closed on the wrong side", "100 * t < 15 * T) return 0.99f", "100 * t <= 15 * T) return 0.99f"),
+    ("lr plateau values swapped", "if (10 * t < 8 * T) return 1.1f;\n    return 0.9f;", "if (10 * t < 8 * T) return 0.9f;\n    return 1.1f;"),
+    ("lr ramp from 0.1 T as fraction of T", "(double)(10 * t - T) / (double)T", "(double)(10 * t - T) / (double)(10 * T)"),
+    ("lazy start ends one step early", "return (10 * t <= T) ? 0 : 1;", "return (10 * t < T) ? 0 : 1;"),
+    ("warmup mu taken from the decay schedule", "if (*phase == 0) { *mu = 0.9f; *lr = 0.0f; }",
+     "if (*phase == 0) { *mu = pier_oracle_mu(t, T); *lr = 0.0f; }"),
+]
+
+
+def battery():
+    calls = [
+        (pins.test_adamw_first_step_closed_form_hand_case, ()),
+        (pins.test_adamw_constant_gradient_closed_form, (10,)),
+        (pins.test_adamw_matches_torch_library, (pins.HP,)),
+        (pins.test_adamw_bf16_gradients_widen_exactly, ()),
+        (pins.test_adamw_grad_scale_is_a_gradient_multiplier, ()),
+        (pins.test_outer_single_group_unit_rate_returns_the_model, ()),
+        (pins.test_outer_unit_rate_no_momentum_is_the_replica_mean, ()),
+        (pins.test_outer_nesterov_two_rounds_by_hand, ()),
+        (pins.test_outer_matches_torch_sgd_nesterov, ()),
+        (pins.test_warmup_accumulates_without_touching_the_model, ()),
+        (pins.test_rounds_against_torch_optimizers, ()),
+    ]
+    calls += [(pins.test_schedules_match_the_printed_constants, (row,)) for row in pins._golden_rows()]
+    return calls
+
+
+def run_battery(oracle):
+    """Names of the pins that fail with ``oracle`` in place of the real one."""
+    saved = pins.O
+    pins.O = oracle
+    failed = []
+    try:
+        for fn, args in battery():
+            try:
+                fn(*args)
+            except AssertionError:
+                failed.append(fn.__name__)
+    finally:
+        pins.O = saved
+    return failed
+
+
+def compile_variant(tmp_path, name, text):
+    c = tmp_path / "variant.c"
+    so = tmp_path / ("variant_%d.so" % abs(hash(name)))
+    c.write_text(text)
+    flags = [f for f in O.CFLAGS if f not in ("-Wall", "-Wextra")]
+    subprocess.check_call(["gcc", *flags, "-w", "-o", str(so), str(c), "-lm"])
+    return O.Oracle(str(so))
+
+
+def test_unmodified_source_passes_the_battery(tmp_path):
+    assert run_battery(compile_variant(tmp_path, "identity", SRC)) == []
+
+
+@pytest.mark.parametrize("name,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_planted_mistake_is_caught(tmp_path, name, old, new):
+    assert SRC.count(old) >= 1, "mutation target not found in the oracle source: " + name
+    broken = compile_variant(tmp_path, name, SRC.replace(old, new, 1))
+    assert run_battery(broken), "no pin notices: " + name

@@ -1,0 +1,333 @@
+"""Pins for the CPU oracle: closed forms, library routines, hand-computed cases and
+the schedule constants the paper prints.  None of these re-types the oracle's own
+expression sequence; each is a different route to the same number."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pier_oracle as O
+
+HP = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def f32(x):
+    return np.ascontiguousarray(np.asarray(x, dtype=np.float32))
+
+
+def tol(ref):
+    """The parity bar: 1e-6 * max(1, |x|)."""
+    return 1e-6 * np.maximum(1.0, np.abs(ref))
+
+
+# ---------------------------------------------------------------- inner AdamW
+
+def test_adamw_first_step_closed_form_hand_case():
+    # m0 = v0 = 0  =>  mhat = g, vhat = g^2  =>  theta1 = theta0 - lr (g/(|g|+eps) + wd theta0)
+    th0 = np.array([0.5, -0.25, 0.0, 2.0])
+    g = np.array([1e-3, -2e-3, 4e-4, 0.0])
+    lr, eps, wd = HP["lr"], HP["eps"], HP["weight_decay"]
+    want = th0 - lr * (g / (np.abs(g) + eps) + wd * th0)
+    # by hand: 0.5 - 3e-4*(~1 + 0.05), -0.25 - 3e-4*(~-1 - 0.025), -3e-4*~1, 2 - 3e-4*0.2
+    np.testing.assert_allclose(want, [0.4996850030, -0.2496925015, -2.999925e-4, 1.99994],
+                               rtol=0, atol=1e-9)
+    p, m, v = f32(th0), f32(np.zeros(4)), f32(np.zeros(4))
+    O.adamw(p, m, v, f32(g), step=1, **HP)
+    np.testing.assert_allclose(p, want, rtol=0, atol=2e-7)
+    # the moments after one step from zero: (1-b1) g and (1-b2) g^2
+    np.testing.assert_allclose(m, 0.1 * g, rtol=1e-6, atol=0)
+    np.testing.assert_allclose(v, 0.05 * g * g, rtol=1e-6, atol=0)
+
+
+@pytest.mark.parametrize("steps", [1, 2, 10, 60])
+def test_adamw_constant_gradient_closed_form(steps):
+    # g constant => mhat_t = g and vhat_t = g^2 for every t, hence
+    # theta_t = (1 - lr wd)^t theta0 - lr s sum_{k<t} (1 - lr wd)^k,  s = g / (|g| + eps)
+    rng = np.random.default_rng(1)
+    th0 = rng.normal(0, 0.02, 64)
+    g = rng.normal(0, 1e-3, 64)
+    lr, eps, wd = HP["lr"], HP["eps"], HP["weight_decay"]
+    q = 1.0 - lr * wd
+    s = g / (np.abs(g) + eps)
+    want = q ** steps * th0 - lr * s * sum(q ** k for k in range(steps))
+    p, m, v = f32(th0), f32(np.zeros(64)), f32(np.zeros(64))
+    for t in range(1, steps + 1):
+        O.adamw(p, m, v, f32(g), step=t, **HP)
+    # fp32 state: each step rounds theta (|theta| ~ 0.02..0.06) and the update once
+    np.testing.assert_allclose(p, want, rtol=0, atol=steps * 1.5e-8)
+    # bias-corrected moments recover g and g^2
+    np.testing.assert_allclose(m / (1 - 0.9 ** steps), f32(g), rtol=2e-6)
+    np.testing.assert_allclose(v / (1 - 0.95 ** steps), f32(g).astype(np.float64) ** 2, rtol=4e-6)
+
+
+@pytest.mark.parametrize("hp", [HP, dict(lr=1.5e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.1)])
+def test_adamw_matches_torch_library(hp):
+    # independent library routine: torch.optim.AdamW, CPU, fp32, per-tensor loop
+    rng = np.random.default_rng(2)
+    n, steps = 100_000, 100
+    th0 = rng.normal(0, 0.02, n).astype(np.float32)
+    p, m, v = th0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    tp = torch.nn.Parameter(torch.from_numpy(th0.copy()))
+    opt = torch.optim.AdamW([tp], lr=hp["lr"], betas=(hp["beta1"], hp["beta2"]), eps=hp["eps"],
+                            weight_decay=hp["weight_decay"], foreach=False, fused=False)
+    for t in range(1, steps + 1):
+        g = rng.normal(0, 1e-3, n).astype(np.float32)
+        O.adamw(p, m, v, g, step=t, **hp)
+        tp.grad = torch.from_numpy(g.copy())
+        opt.step()
+    ref = tp.detach().numpy()
+    assert np.all(np.abs(p - ref) <= tol(ref))
+    # torch multiplies theta by the fp32-rounded factor (1 - lr wd) each step, a systematic
+    # ~3e-8 relative offset per step; the float64 recurrence below is the tight pin
+    assert np.max(np.abs(p - ref)) < 5e-7
+    st = opt.state[tp]
+    np.testing.assert_allclose(m, st["exp_avg"].numpy(), rtol=1e-5, atol=1e-9)   # torch lerps: differs near m = 0
+    # float(0.999) is 0.99900001, so 1 - beta2 formed from the fp32 value sits 1.3e-5 below torch's double 0.001
+    np.testing.assert_allclose(v, st["exp_avg_sq"].numpy(), rtol=3e-5, atol=1e-14)
+    assert np.max(np.abs(p - th0)) > 1e-3         # and the 100 steps did move the model
+
+
+def test_adamw_matches_float64_recurrence():
+    # the same rule evaluated in float64 throughout: fp32 rounding stays within the bar
+    rng = np.random.default_rng(3)
+    n, steps = 4096, 200
+    th = rng.normal(0, 0.02, n)
+    m64, v64 = np.zeros(n), np.zeros(n)
+    p, m, v = f32(th), f32(m64), f32(v64)
+    b1, b2, lr, eps, wd = (float(np.float32(HP[k])) for k in ("beta1", "beta2", "lr", "eps", "weight_decay"))
+    th = p.astype(np.float64)
+    for t in range(1, steps + 1):
+        g = rng.normal(0, 1e-3, n).astype(np.float32)
+        O.adamw(p, m, v, g, step=t, **HP)
+        g64 = g.astype(np.float64)
+        m64 = b1 * m64 + (1 - b1) * g64
+        v64 = b2 * v64 + (1 - b2) * g64 * g64
+        th = th - lr * (m64 / (1 - b1 ** t) / (np.sqrt(v64 / (1 - b2 ** t)) + eps) + wd * th)
+    assert np.all(np.abs(p - th) <= tol(th))
+    np.testing.assert_allclose(m, m64, rtol=2e-6, atol=2e-10)   # m ~ 3e-4, its fp32 ulp ~ 3e-11
+    np.testing.assert_allclose(v, v64, rtol=5e-6, atol=1e-16)
+
+
+def test_adamw_bf16_gradients_widen_exactly():
+    from pier_inputs import generator as gen
+    rng = np.random.default_rng(4)
+    n = 1000
+    g = rng.normal(0, 1e-3, n).astype(np.float32)
+    gb = gen.to_bf16_bits(g)
+    gw = gen.bf16_bits_to_f32(gb)
+    assert np.max(np.abs(gw - g)) <= np.max(np.abs(g)) * 2 ** -8
+    # torch's own bf16 rounding is the independent check of the bit patterns
+    tb = torch.from_numpy(g).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(tb, gb)
+    a = [rng.normal(0, 0.02, n).astype(np.float32), np.zeros(n, np.float32), np.zeros(n, np.float32)]
+    b = [x.copy() for x in a]
+    for t in (1, 2, 3):
+        O.adamw(*a, gb, step=t, **HP)
+        O.adamw(*b, gw, step=t, **HP)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+def test_adamw_grad_scale_is_a_gradient_multiplier():
+    rng = np.random.default_rng(5)
+    n = 512
+    g = rng.normal(0, 1e-3, n).astype(np.float32)
+    a = [rng.normal(0, 0.02, n).astype(np.float32), np.zeros(n, np.float32), np.zeros(n, np.float32)]
+    b = [x.copy() for x in a]
+    O.adamw(*a, g, step=1, grad_scale=0.25, **HP)          # power of two: scaling is exact
+    O.adamw(*b, (g * np.float32(0.25)).astype(np.float32), step=1, **HP)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+# ---------------------------------------------------------------- outer step
+
+def test_outer_single_group_unit_rate_returns_the_model():
+    # G = 1, M = 0, mu = 0, lr = 1: plain AdamW plus the anchor copy
+    rng = np.random.default_rng(6)
+    n = 1000
+    a0 = rng.normal(0, 0.02, n).astype(np.float32)
+    th = (a0 + rng.normal(0, 1e-3, n)).astype(np.float32)
+    for ph in (O.WARMUP, O.PIER):
+        a, M, t = a0.copy(), np.zeros(n, np.float32), th.copy()
+        O.outer([t], a, M, mu=0.0, lr=1.0, phase=ph)
+        if ph == O.WARMUP:
+            assert np.array_equal(a, th) and np.array_equal(t, th)
+        else:
+            assert np.max(np.abs(a - th)) <= 2 ** -29      # a + (theta - a): within an ulp of 0.06
+            assert np.array_equal(t, a)
+        np.testing.assert_allclose(M, th.astype(np.float64) - a0, rtol=0, atol=1e-9)
+
+
+def test_outer_unit_rate_no_momentum_is_the_replica_mean():
+    rng = np.random.default_rng(7)
+    n, G = 777, 4
+    a0 = rng.normal(0, 0.02, n).astype(np.float32)
+    ths = [(a0 + rng.normal(0, 1e-3, n)).astype(np.float32) for _ in range(G)]
+    mean = np.mean(np.stack(ths).astype(np.float64), axis=0)
+    a, M = a0.copy(), (rng.normal(0, 1e-3, n)).astype(np.float32)   # mu = 0 must ignore old M
+    t = [x.copy() for x in ths]
+    O.outer(t, a, M, mu=0.0, lr=1.0, phase=O.PIER)
+    np.testing.assert_allclose(a, mean, rtol=0, atol=4e-9)
+    for x in t:
+        assert np.array_equal(x, a)                        # every group re-synchronised
+    np.testing.assert_allclose(M, mean - a0, rtol=0, atol=1e-9)
+    # identical replicas, power-of-two G: the warmup anchor is bitwise the model
+    same = [ths[0].copy() for _ in range(G)]
+    a = a0.copy()
+    O.outer(same, a, np.zeros(n, np.float32), mu=0.9, lr=0.0, phase=O.WARMUP)
+    assert np.array_equal(a, ths[0])
+
+
+def test_outer_nesterov_two_rounds_by_hand():
+    # a = 0, M = 0, lr = 0.7, mu = 0.9, one group, exactly representable deltas.
+    # round 1: delta1 = 0.5          M1 = 0.5      theta1 = 0.7 (0.9*0.5 + 0.5) = 0.665
+    # round 2: model moved by 0.25   M2 = 0.9*0.5 + 0.25 = 0.7
+    #          theta2 = 0.665 + 0.7 (0.9*0.7 + 0.25) = 0.665 + 0.616 = 1.281
+    a, M = f32([0.0]), f32([0.0])
+    th = f32([0.5])
+    O.outer([th], a, M, mu=0.9, lr=0.7, phase=O.PIER)
+    assert abs(M[0] - 0.5) < 1e-7 and abs(a[0] - 0.665) < 1e-7 and th[0] == a[0]
+    th[0] = np.float32(th[0] + np.float32(0.25))
+    O.outer([th], a, M, mu=0.9, lr=0.7, phase=O.PIER)
+    assert abs(M[0] - 0.7) < 1e-7
+    assert abs(a[0] - 1.281) < 2e-7 and th[0] == a[0]
+
+
+def test_outer_matches_torch_sgd_nesterov():
+    # library routine: SGD(momentum, nesterov=True) fed the gradient a - mean(theta);
+    # its buffer is -M and its parameter is the anchor
+    rng = np.random.default_rng(8)
+    n, G = 5000, 8
+    a0 = rng.normal(0, 0.02, n).astype(np.float32)
+    a, M = a0.copy(), np.zeros(n, np.float32)
+    tp = torch.nn.Parameter(torch.from_numpy(a0.copy()))
+    sched = [(0.99, 0.3), (0.95, 0.8), (0.9, 1.1), (0.9, 0.9)]
+    for k, (mu, lr) in enumerate(sched):
+        ths = [(a + rng.normal(0, 2e-3, n)).astype(np.float32) for _ in range(G)]
+        mean = torch.from_numpy(np.mean(np.stack(ths).astype(np.float64), axis=0).astype(np.float32))
+        opt = torch.optim.SGD([tp], lr=lr, momentum=mu, nesterov=True)
+        if k:
+            opt.state[tp]["momentum_buffer"] = buf
+        tp.grad = tp.detach() - mean
+        opt.step()
+        buf = opt.state[tp]["momentum_buffer"]
+        O.outer(ths, a, M, mu=mu, lr=lr, phase=O.PIER)
+        ref = tp.detach().numpy()
+        assert np.all(np.abs(a - ref) <= tol(ref)), k
+        assert np.max(np.abs(a - ref)) < 2e-8
+        np.testing.assert_allclose(M, -buf.numpy(), rtol=1e-5, atol=1e-8)  # the library rounds the mean to fp32 first
+        for x in ths:
+            assert np.array_equal(x, a)
+
+
+def test_warmup_accumulates_without_touching_the_model():
+    rng = np.random.default_rng(9)
+    n, G, K = 300, 2, 5
+    th = rng.normal(0, 0.02, n).astype(np.float32)
+    a, M, M1 = th.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    a1 = th.copy()
+    th0 = th.copy()
+    deltas = []
+    for _ in range(K):
+        new = (th + rng.normal(0, 1e-3, n)).astype(np.float32)
+        deltas.append(new.astype(np.float64) - th)
+        th = new
+        reps = [th.copy() for _ in range(G)]
+        O.outer(reps, a, M, mu=0.9, lr=123.0, phase=O.WARMUP)    # lr must be ignored
+        for r in reps:
+            assert np.array_equal(r, th)                           # model not updated
+        assert np.array_equal(a, th)                               # anchor follows the model
+        O.outer([th.copy()], a1, M1, mu=1.0, lr=0.0, phase=O.WARMUP)
+    want = sum(0.9 ** (K - 1 - j) * d for j, d in enumerate(deltas))   # M = sum mu^(k-j) delta_j
+    np.testing.assert_allclose(M, want, rtol=0, atol=5e-9)
+    np.testing.assert_allclose(M1, th.astype(np.float64) - th0, rtol=0, atol=5e-9)  # mu = 1 telescopes
+
+
+def test_difference_then_mean_equals_mean_then_difference():
+    # the all-reduce may average differences or difference the average: same number
+    rng = np.random.default_rng(10)
+    n, G = 2048, 8
+    a0 = rng.normal(0, 0.02, n).astype(np.float32)
+    ths = [(a0 + rng.normal(0, 1e-3, n)).astype(np.float32) for _ in range(G)]
+    a, M = a0.copy(), np.zeros(n, np.float32)
+    O.outer([t.copy() for t in ths], a, M, mu=0.9, lr=0.7, phase=O.PIER)
+    d = np.mean(np.stack(ths).astype(np.float64), axis=0) - a0
+    want = a0 + 0.7 * 1.9 * d
+    assert np.all(np.abs(a - want) <= tol(want))
+    assert np.max(np.abs(a - want)) < 1e-8
+
+
+# ---------------------------------------------------------------- whole rounds
+
+def test_rounds_against_torch_optimizers():
+    """H inner steps per group then an outer step, three rounds: AdamW moments and
+    the step count carry across outer steps; checked against torch's two optimizers."""
+    rng = np.random.default_rng(11)
+    n, G, H = 3000, 2, 5
+    th0 = rng.normal(0, 0.02, n).astype(np.float32)
+    P = [th0.copy() for _ in range(G)]
+    Mo = [np.zeros(n, np.float32) for _ in range(G)]
+    V = [np.zeros(n, np.float32) for _ in range(G)]
+    a, M = th0.copy(), np.zeros(n, np.float32)
+    tps = [torch.nn.Parameter(torch.from_numpy(th0.copy())) for _ in range(G)]
+    inner = [torch.optim.AdamW([tp], lr=HP["lr"], betas=(0.9, 0.95), eps=1e-8, weight_decay=0.1,
+                               foreach=False) for tp in tps]
+    anchor = torch.nn.Parameter(torch.from_numpy(th0.copy()))
+    outer = torch.optim.SGD([anchor], lr=0.7, momentum=0.9, nesterov=True)
+    t = 0
+    for _ in range(3):
+        for _ in range(H):
+            t += 1
+            for g in range(G):
+                gr = rng.normal(0, 1e-3, n).astype(np.float32)
+                O.adamw(P[g], Mo[g], V[g], gr, step=t, **HP)
+                tps[g].grad = torch.from_numpy(gr.copy())
+                inner[g].step()
+        O.outer(P, a, M, mu=0.9, lr=0.7, phase=O.PIER)
+        with torch.no_grad():
+            anchor.grad = anchor.detach() - torch.stack([tp.detach() for tp in tps]).mean(0)
+            outer.step()
+            for tp in tps:
+                tp.copy_(anchor)
+        ref = anchor.detach().numpy()
+        assert np.all(np.abs(a - ref) <= tol(ref))
+        assert np.max(np.abs(a - ref)) < 2e-7        # torch's rounded decay factor, see above
+        assert all(np.array_equal(p, a) for p in P)
+
+
+# ---------------------------------------------------------------- schedules
+
+def _golden_rows():
+    rows = []
+    with open(os.path.join(GOLDEN, "schedules.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                t, T, ph, mu, lr = line.split()
+                rows.append((int(t), int(T), int(ph), float(mu), float(lr)))
+    return rows
+
+
+@pytest.mark.parametrize("row", _golden_rows())
+def test_schedules_match_the_printed_constants(row):
+    t, T, ph, mu, lr = row
+    assert O.phase(t, T) == ph
+    assert O.mu(t, T) == np.float32(mu)
+    assert abs(O.outer_lr(t, T) - lr) <= 1e-7
+    p2, mu2, lr2 = O.outer_scalars(t, T)
+    assert p2 == ph
+    if ph == 0:
+        assert mu2 == np.float32(0.9) and lr2 == 0.0       # Algorithm 1's default mu
+    else:
+        assert mu2 == np.float32(mu) and abs(lr2 - lr) <= 1e-7
+
+
+def test_schedule_is_monotone_where_the_paper_says_so():
+    T = 1000
+    mus = [O.mu(t, T) for t in range(100, T + 1)]
+    assert all(x >= y for x, y in zip(mus, mus[1:]))          # 0.99 -> 0.95 -> 0.9
+    lrs = [O.outer_lr(t, T) for t in range(100, 200)]
+    assert all(x < y for x, y in zip(lrs, lrs[1:])) and lrs[0] == 0.0 and lrs[-1] < 1.0
