@@ -1,0 +1,177 @@
+/*
+ * pier.h - C ABI of the MI355X (gfx950) implementation of the optimizer hot path
+ * of Pier's two-level optimizer: the inner AdamW step of every group replica, the
+ * outer Nesterov step with momentum warmup / momentum decay, and the host-offload
+ * stream for the outer state.
+ *
+ * Notation (the paper's): theta_g = model of group g, G groups; theta_{t-r} = the
+ * model at the previous synchronisation, here "anchor"; M = outer momentum;
+ * r = synchronisation interval; T = training iterations; mu = momentum coefficient.
+ *
+ * Conventions
+ *  - Every function returns a pier_status and never throws or aborts across the
+ *    ABI; pier_last_error() gives the reason of the calling thread's last failure.
+ *  - All argument checks happen before anything is enqueued: a call that returns an
+ *    error has launched nothing and changed no buffer.
+ *  - "device pointer" = memory of the GPU that was current when the context first
+ *    touched the GPU (first bind call); the caller keeps that device current for
+ *    every later call.  "host pointer" = ordinary host memory unless "pinned" is said.
+ *  - Ownership: the caller owns all parameter, state, gradient, staging and pinned
+ *    memory and all streams.  The library owns only small tables (pointer lists,
+ *    chunk lists, events) that live as long as the context.
+ *  - Kernels and copies are enqueued on the caller's streams; calls do not
+ *    synchronise unless stated.  hip_stream arguments are hipStream_t values passed
+ *    as void* (NULL = the null stream).
+ *  - All model-sized buffers are fp32, updated in place.  A model is a list of
+ *    n_tensors separately allocated tensors; tensor i has numel[i] elements.  A
+ *    pointer must be aligned to its element size; 16-byte aligned tensors take the
+ *    128-bit path, others a slower scalar path with identical results.
+ *  - Results are deterministic: they do not depend on chunking, grid size, or the
+ *    offload chunk size; the sum over groups always runs g = 0, 1, ..., G-1.
+ */
+#ifndef PIER_H
+#define PIER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PIER_OK = 0,
+    PIER_ERR_INVALID_ARG = 1, /* null / negative / out-of-range argument            */
+    PIER_ERR_ALIGNMENT = 2,   /* pointer not aligned to its element size            */
+    PIER_ERR_STATE = 3,       /* call made before the bindings it needs             */
+    PIER_ERR_OOM = 4,         /* a table or event could not be allocated            */
+    PIER_ERR_HIP = 5          /* the HIP runtime reported an error (text in last_error) */
+} pier_status;
+
+/* Text of the calling thread's most recent error; never NULL; valid until the
+ * thread's next failing call. */
+const char* pier_last_error(void);
+/* Name of a status code ("PIER_OK", ...); never NULL. */
+const char* pier_status_string(pier_status s);
+
+/* ----------------------------------------------------------------- context */
+
+typedef struct pier_ctx pier_ctx; /* opaque */
+
+/* Describes the model: n_tensors >= 1 tensors with numel[i] >= 0 elements (host
+ * array, copied), held by n_replicas >= 1 group replicas (at most
+ * PIER_MAX_REPLICAS).  Host-only: touches no GPU. */
+#define PIER_MAX_REPLICAS 64
+pier_status pier_ctx_create(pier_ctx** out, int n_tensors, const int64_t* numel, int n_replicas);
+/* Frees the library's tables and events.  Caller buffers are not touched.  The
+ * caller must have drained the streams it used with this context. */
+pier_status pier_ctx_destroy(pier_ctx* ctx);
+/* Sum of numel (the parameter count N); -1 if ctx is NULL. */
+int64_t pier_ctx_numel(const pier_ctx* ctx);
+
+/* Launch shape of the kernels; defaults suit MI355X and results never depend on it.
+ * chunk_elems: elements one workgroup handles per chunk (multiple of 1024, >= 1024);
+ * unroll: 128-bit loads each lane keeps in flight per stream (1, 2 or 4);
+ * max_grid: cap on workgroups per launch (0 = one chunk per workgroup);
+ * nontemporal: 1 = mark loads/stores as streaming.  Pass 0 / -1 (nontemporal) to keep
+ * a field unchanged.  Must be called before the first bind. */
+pier_status pier_ctx_set_launch(pier_ctx* ctx, int64_t chunk_elems, int unroll, int max_grid,
+                                int nontemporal);
+
+/* Binds replica `replica` (0-based).  p, m, v, grad are HOST arrays of n_tensors
+ * DEVICE pointers: parameters theta_g, AdamW first and second moments (fp32), and
+ * the gradient of each tensor, fp32 or (grad_is_bf16 != 0) bfloat16.  A tensor with
+ * numel 0 may have NULL pointers.  May be called again to re-point a replica
+ * (synchronous small copy). */
+pier_status pier_bind_replica(pier_ctx* ctx, int replica, float* const* p, float* const* m,
+                              float* const* v, const void* const* grad, int grad_is_bf16);
+
+typedef enum {
+    PIER_LOC_DEVICE = 0,     /* anchor[i], momentum[i]: device pointer of tensor i      */
+    PIER_LOC_HOST_PINNED = 1 /* anchor[0], momentum[0]: one flat PINNED host array each,
+                                N floats, tensors back to back in list order          */
+} pier_loc;
+/* Binds the outer optimizer's state: the anchor theta_{t-r} and the momentum M.
+ * The arrays `anchor` / `momentum` themselves are host arrays (n_tensors entries
+ * for DEVICE, 1 entry for HOST_PINNED). */
+pier_status pier_bind_outer(pier_ctx* ctx, pier_loc loc, float* const* anchor,
+                            float* const* momentum);
+
+/* ------------------------------------------------------- inner AdamW step
+ * One AdamW update of replica `replica` (Algorithm 1 / Algorithm 2,
+ * "OptimizerUpdate"; section "Implementation": AdamW inside each group; Table I).
+ * Per element, in fp32:
+ *     g  = grad * grad_scale
+ *     m  = beta1 m + (1 - beta1) g          v = beta2 v + (1 - beta2) g^2
+ *     mh = m / (1 - beta1^step)             vh = v / (1 - beta2^step)
+ *     theta = theta - lr * ( mh / (sqrt(vh) + eps) + weight_decay * theta )
+ * step >= 1 is the global iteration count (moments are never reset by an outer step).
+ * One kernel launch over the whole tensor list on `hip_stream`. */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    float grad_scale; /* 1 on the plain path; multiplies every gradient element */
+    int64_t step;
+} pier_adamw_hp;
+pier_status pier_inner_adamw(pier_ctx* ctx, int replica, const pier_adamw_hp* hp, void* hip_stream);
+
+/* ----------------------------------------------------------- outer step
+ * Algorithm 2's synchronisation branch (PIER) and Algorithm 1's (WARMUP), fused
+ * into one kernel over all replicas, with anchor and M on the device:
+ *     delta = (1/G) sum_g (theta_g - anchor)          [the all-reduce's arithmetic]
+ *     M     = mu M + delta
+ *   PIER:   theta = anchor + outer_lr (mu M + delta); anchor = theta_g = theta for all g
+ *   WARMUP: anchor = (1/G) sum_g theta_g; replicas untouched; outer_lr ignored
+ * M holds the paper's sign (it accumulates new - old).  Needs every replica bound
+ * and pier_bind_outer(PIER_LOC_DEVICE). */
+typedef enum { PIER_PHASE_WARMUP = 0, PIER_PHASE_PIER = 1 } pier_phase;
+typedef struct {
+    float outer_lr, mu;
+    pier_phase phase;
+} pier_outer_hp;
+pier_status pier_outer_step(pier_ctx* ctx, const pier_outer_hp* hp, void* hip_stream);
+
+/* ------------------------------------------------- host-offload outer step
+ * The same outer step with anchor and M resident in pinned host memory (section
+ * "Implementation": the previous model and the outer momentum are offloaded to the
+ * host, reloaded at the start of the outer step and written back at its end).  The
+ * flat index space is cut into pieces of chunk_bytes (multiple of 16; 256 MiB is the
+ * intended size); piece k is copied host->device on h2d_stream, processed by the
+ * outer kernel on compute_stream and copied back on d2h_stream, the three stages of
+ * different pieces overlapping.  `workspace` is caller-owned device memory holding
+ * the staging slots (2 arrays x chunk_bytes per slot; 1 to 4 slots are used, 3
+ * recommended = pier_offload_workspace_bytes).  Results are bit-identical to
+ * pier_outer_step.  compute_stream is made to wait for the last copy-back, so work
+ * enqueued on it afterwards sees both the replicas and the host arrays complete; the
+ * call itself returns after enqueueing unless `stats` is non-NULL, in which case it
+ * waits for completion and fills the timings (milliseconds, bytes; *_ms are the
+ * summed durations of that stage's operations, wall_ms first copy-in to last
+ * copy-back).  The three streams must be distinct for overlap but need not be.
+ * Needs pier_bind_outer(PIER_LOC_HOST_PINNED).  The first call with a new
+ * chunk_bytes builds and uploads that chunking's tables (a small synchronous copy). */
+typedef struct {
+    double h2d_bytes, d2h_bytes, h2d_ms, d2h_ms, kernel_ms, wall_ms;
+    int n_pieces, n_slots;
+} pier_offload_stats;
+pier_status pier_offload_workspace_bytes(const pier_ctx* ctx, size_t chunk_bytes, size_t* out);
+pier_status pier_offload_stream(pier_ctx* ctx, const pier_outer_hp* hp, size_t chunk_bytes,
+                                void* workspace, size_t workspace_bytes, void* compute_stream,
+                                void* h2d_stream, void* d2h_stream, pier_offload_stats* stats);
+
+/* ------------------------------------------------------------- schedules
+ * Pure host helpers; t = iteration (1-based), T = total iterations (> 0). */
+
+/* Algorithm 2's momentum-decay choice: 0.99 for 0.1T <= t < 0.15T, 0.95 for
+ * 0.15T <= t < 0.2T, 0.9 otherwise (breakpoints compared in integers). */
+float pier_mu_schedule(int64_t t, int64_t T);
+/* Section "Implementation": 0 below 0.1T, linear 0 -> 1 on [0.1T, 0.2T), 1.1 on
+ * [0.2T, 0.8T), 0.9 on [0.8T, T]. */
+float pier_outer_lr_schedule(int64_t t, int64_t T);
+/* Fills the scalars of the synchronisation at iteration t: lazy-start phase
+ * (t <= 0.1T, Algorithm 1's inclusive loop bound) -> WARMUP with Algorithm 1's
+ * default mu = 0.9; afterwards PIER with the two schedules above. */
+pier_status pier_outer_schedule(int64_t t, int64_t T, pier_outer_hp* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIER_H */

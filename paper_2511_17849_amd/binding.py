@@ -1,0 +1,212 @@
+"""ctypes binding of libpier.so.  Functions carry the names of include/pier.h and do
+argument marshalling only: lists of torch tensors become arrays of device pointers,
+streams become hipStream_t handles, status codes become exceptions.  Every step of
+the optimizer path runs in the HIP library."""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpier.so")
+
+PIER_PHASE_WARMUP, PIER_PHASE_PIER = 0, 1
+PIER_LOC_DEVICE, PIER_LOC_HOST_PINNED = 0, 1
+
+
+class PierError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("%s: %s" % (status, message))
+        self.status = status
+
+
+class AdamwHP(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float),
+                ("grad_scale", ctypes.c_float), ("step", ctypes.c_int64)]
+
+
+class OuterHP(ctypes.Structure):
+    _fields_ = [("outer_lr", ctypes.c_float), ("mu", ctypes.c_float), ("phase", ctypes.c_int)]
+
+
+class OffloadStats(ctypes.Structure):
+    _fields_ = [("h2d_bytes", ctypes.c_double), ("d2h_bytes", ctypes.c_double),
+                ("h2d_ms", ctypes.c_double), ("d2h_ms", ctypes.c_double),
+                ("kernel_ms", ctypes.c_double), ("wall_ms", ctypes.c_double),
+                ("n_pieces", ctypes.c_int), ("n_slots", ctypes.c_int)]
+
+
+_lib = None
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libpier.so is not built: run `python -m paper_2511_17849_amd.build` "
+                          "(or __graft_entry__.build()); there is no fallback path")
+    # torch ships its own HIP runtime; import it first so that libpier binds to the
+    # runtime that owns torch's allocations and streams
+    import torch  # noqa: F401
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
+    pp = ctypes.POINTER(ctypes.c_void_p)
+    sig = {
+        "pier_last_error": (ctypes.c_char_p, []),
+        "pier_status_string": (ctypes.c_char_p, [i32]),
+        "pier_ctx_create": (i32, [ctypes.POINTER(vp), i32, ctypes.POINTER(i64), i32]),
+        "pier_ctx_destroy": (i32, [vp]),
+        "pier_ctx_numel": (i64, [vp]),
+        "pier_ctx_set_launch": (i32, [vp, i64, i32, i32, i32]),
+        "pier_bind_replica": (i32, [vp, i32, pp, pp, pp, pp, i32]),
+        "pier_bind_outer": (i32, [vp, i32, pp, pp]),
+        "pier_inner_adamw": (i32, [vp, i32, ctypes.POINTER(AdamwHP), vp]),
+        "pier_outer_step": (i32, [vp, ctypes.POINTER(OuterHP), vp]),
+        "pier_offload_workspace_bytes": (i32, [vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]),
+        "pier_offload_stream": (i32, [vp, ctypes.POINTER(OuterHP), ctypes.c_size_t, vp, ctypes.c_size_t,
+                                      vp, vp, vp, ctypes.POINTER(OffloadStats)]),
+        "pier_mu_schedule": (f32, [i64, i64]),
+        "pier_outer_lr_schedule": (f32, [i64, i64]),
+        "pier_outer_schedule": (i32, [i64, i64, ctypes.POINTER(OuterHP)]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = L
+    return L
+
+
+def pier_last_error():
+    return _load().pier_last_error().decode()
+
+
+def pier_status_string(status):
+    return _load().pier_status_string(int(status)).decode()
+
+
+def _check(status):
+    if status != 0:
+        raise PierError(pier_status_string(status), pier_last_error())
+
+
+class PierCtx:
+    """Handle of a pier_ctx.  Keeps the bound tensors alive."""
+
+    def __init__(self, handle):
+        self.handle = handle
+        self._keep = {}
+
+    def __del__(self):
+        try:
+            pier_ctx_destroy(self)
+        except Exception:
+            pass
+
+
+def _ptr_array(items):
+    """Host array of pointers from torch tensors, raw ints or None."""
+    vals = []
+    for x in items:
+        if x is None:
+            vals.append(None)
+        elif isinstance(x, int):
+            vals.append(x or None)
+        else:
+            vals.append(x.data_ptr() or None)
+    return (ctypes.c_void_p * len(vals))(*vals)
+
+
+def _stream(s):
+    """hipStream_t of a torch.cuda.Stream, a raw handle, or None (null stream)."""
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s or None
+    return s.cuda_stream or None
+
+
+def pier_ctx_create(numel, n_replicas):
+    L = _load()
+    arr = (ctypes.c_int64 * len(numel))(*[int(n) for n in numel])
+    h = ctypes.c_void_p()
+    _check(L.pier_ctx_create(ctypes.byref(h), len(numel), arr, int(n_replicas)))
+    return PierCtx(h)
+
+
+def pier_ctx_destroy(ctx):
+    if ctx.handle:
+        h, ctx.handle = ctx.handle, None
+        ctx._keep.clear()
+        _check(_load().pier_ctx_destroy(h))
+
+
+def pier_ctx_numel(ctx):
+    return _load().pier_ctx_numel(ctx.handle)
+
+
+def pier_ctx_set_launch(ctx, chunk_elems=0, unroll=0, max_grid=0, nontemporal=-1):
+    _check(_load().pier_ctx_set_launch(ctx.handle, int(chunk_elems), int(unroll), int(max_grid),
+                                       int(nontemporal)))
+
+
+def pier_bind_replica(ctx, replica, p, m, v, grad, grad_is_bf16=False):
+    ctx._keep[("rep", replica)] = (list(p), list(m), list(v), list(grad))
+    _check(_load().pier_bind_replica(ctx.handle, int(replica), _ptr_array(p), _ptr_array(m),
+                                     _ptr_array(v), _ptr_array(grad), 1 if grad_is_bf16 else 0))
+
+
+def pier_bind_outer(ctx, loc, anchor, momentum):
+    if loc == PIER_LOC_HOST_PINNED and not isinstance(anchor, (list, tuple)):
+        anchor, momentum = [anchor], [momentum]
+    ctx._keep["outer"] = (list(anchor), list(momentum))
+    _check(_load().pier_bind_outer(ctx.handle, int(loc), _ptr_array(anchor), _ptr_array(momentum)))
+
+
+def pier_inner_adamw(ctx, replica, *, lr, beta1, beta2, eps, weight_decay, step, grad_scale=1.0,
+                     stream=None):
+    hp = AdamwHP(lr, beta1, beta2, eps, weight_decay, grad_scale, int(step))
+    _check(_load().pier_inner_adamw(ctx.handle, int(replica), ctypes.byref(hp), _stream(stream)))
+
+
+def pier_outer_step(ctx, *, outer_lr, mu, phase, stream=None):
+    hp = OuterHP(outer_lr, mu, int(phase))
+    _check(_load().pier_outer_step(ctx.handle, ctypes.byref(hp), _stream(stream)))
+
+
+def pier_offload_workspace_bytes(ctx, chunk_bytes):
+    out = ctypes.c_size_t()
+    _check(_load().pier_offload_workspace_bytes(ctx.handle, int(chunk_bytes), ctypes.byref(out)))
+    return out.value
+
+
+def pier_offload_stream(ctx, *, outer_lr, mu, phase, chunk_bytes, workspace, compute_stream=None,
+                        h2d_stream=None, d2h_stream=None, want_stats=False):
+    """workspace: a torch uint8/float tensor on the device (or (ptr, nbytes))."""
+    hp = OuterHP(outer_lr, mu, int(phase))
+    if isinstance(workspace, tuple):
+        wptr, wbytes = workspace
+    else:
+        wptr, wbytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    stats = OffloadStats() if want_stats else None
+    _check(_load().pier_offload_stream(ctx.handle, ctypes.byref(hp), int(chunk_bytes), wptr or None,
+                                       int(wbytes), _stream(compute_stream), _stream(h2d_stream),
+                                       _stream(d2h_stream), ctypes.byref(stats) if want_stats else None))
+    return stats
+
+
+def pier_mu_schedule(t, T):
+    return _load().pier_mu_schedule(int(t), int(T))
+
+
+def pier_outer_lr_schedule(t, T):
+    return _load().pier_outer_lr_schedule(int(t), int(T))
+
+
+def pier_outer_schedule(t, T):
+    hp = OuterHP()
+    _check(_load().pier_outer_schedule(int(t), int(T), ctypes.byref(hp)))
+    return hp

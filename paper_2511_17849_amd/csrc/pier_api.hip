@@ -1,0 +1,588 @@
+// Host side of libpier: the C ABI declared in include/pier.h.  Owns only small
+// tables (chunk lists, per-tensor pointer lists, events); every model-sized buffer
+// belongs to the caller.
+#include "../../include/pier.h"
+#include "pier_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace pier;
+
+namespace {
+
+thread_local std::string g_last_error = "";
+
+pier_status fail(pier_status st, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return st;
+}
+
+#define PIER_HIP(call)                                                                      \
+    do {                                                                                    \
+        hipError_t e_ = (call);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return fail(e_ == hipErrorOutOfMemory ? PIER_ERR_OOM : PIER_ERR_HIP, "%s: %s",  \
+                        #call, hipGetErrorString(e_));                                      \
+    } while (0)
+
+// Chunking of one offload piece size: the flat index space cut into pieces, each
+// piece owning a contiguous run of chunk-table entries.
+struct OffloadPlan {
+    int64_t piece_elems = 0;
+    std::vector<int64_t> piece_lo;      // n_pieces + 1 flat element bounds
+    std::vector<int> chunk_begin;       // n_pieces + 1 indices into the chunk table
+    Chunk* d_chunks = nullptr;
+    std::vector<hipEvent_t> ev;         // 6 per piece: h2d b/e, kernel b/e, d2h b/e
+};
+
+}  // namespace
+
+struct pier_ctx {
+    int n_tensors = 0;
+    int n_replicas = 0;
+    std::vector<int64_t> numel;
+    std::vector<int64_t> flat_start;  // n_tensors + 1
+    int64_t N = 0;
+
+    int64_t chunk_elems = 16384;
+    LaunchShape shape{4, 0, 1};
+
+    int device = -1;  // set by the first call that touches the GPU
+    std::vector<Chunk> h_chunks;
+    Chunk* d_chunks = nullptr;
+    int n_chunks = 0;
+
+    std::vector<RepPtrs> h_rep;  // n_replicas * n_tensors, replica-major
+    RepPtrs* d_rep = nullptr;
+    std::vector<char> rep_bound;
+    std::vector<char> rep_bf16;
+
+    std::vector<OuterPtrs> h_outer;
+    OuterPtrs* d_outer = nullptr;
+    bool outer_bound = false;
+    pier_loc outer_loc = PIER_LOC_DEVICE;
+    float* host_a = nullptr;
+    float* host_M = nullptr;
+
+    std::map<size_t, OffloadPlan> plans;
+    hipEvent_t offload_done = nullptr;  // end of the previous offload call's copy-back
+    bool offload_done_valid = false;
+};
+
+namespace {
+
+void build_chunks(const pier_ctx* c, int64_t lo, int64_t hi, std::vector<Chunk>& out)
+{
+    // chunks covering flat elements [lo, hi), never crossing a tensor boundary
+    int t = static_cast<int>(std::upper_bound(c->flat_start.begin(), c->flat_start.end(), lo) -
+                             c->flat_start.begin()) - 1;
+    if (t < 0) t = 0;
+    for (; t < c->n_tensors && c->flat_start[t] < hi; ++t) {
+        const int64_t b = std::max(lo, c->flat_start[t]) - c->flat_start[t];
+        const int64_t e = std::min(hi, c->flat_start[t + 1]) - c->flat_start[t];
+        for (int64_t off = b; off < e; off += c->chunk_elems) {
+            Chunk ch;
+            ch.off = off;
+            ch.tensor = t;
+            ch.len = static_cast<int32_t>(std::min<int64_t>(c->chunk_elems, e - off));
+            out.push_back(ch);
+        }
+    }
+}
+
+pier_status ensure_device(pier_ctx* c)
+{
+    int dev = -1;
+    PIER_HIP(hipGetDevice(&dev));
+    if (c->device >= 0) {
+        if (dev != c->device)
+            return fail(PIER_ERR_STATE, "context belongs to device %d but device %d is current",
+                        c->device, dev);
+        return PIER_OK;
+    }
+    c->h_chunks.clear();
+    build_chunks(c, 0, c->N, c->h_chunks);
+    if (c->h_chunks.size() > static_cast<size_t>(INT32_MAX))
+        return fail(PIER_ERR_INVALID_ARG, "too many chunks; raise chunk_elems");
+    c->n_chunks = static_cast<int>(c->h_chunks.size());
+    if (c->n_chunks > 0) {
+        PIER_HIP(hipMalloc(reinterpret_cast<void**>(&c->d_chunks), sizeof(Chunk) * c->n_chunks));
+        PIER_HIP(hipMemcpy(c->d_chunks, c->h_chunks.data(), sizeof(Chunk) * c->n_chunks,
+                           hipMemcpyHostToDevice));
+    }
+    const size_t nrep = static_cast<size_t>(c->n_replicas) * c->n_tensors;
+    PIER_HIP(hipMalloc(reinterpret_cast<void**>(&c->d_rep), sizeof(RepPtrs) * nrep));
+    PIER_HIP(hipMemset(c->d_rep, 0, sizeof(RepPtrs) * nrep));
+    PIER_HIP(hipMalloc(reinterpret_cast<void**>(&c->d_outer), sizeof(OuterPtrs) * c->n_tensors));
+    PIER_HIP(hipMemcpy(c->d_outer, c->h_outer.data(), sizeof(OuterPtrs) * c->n_tensors,
+                       hipMemcpyHostToDevice));
+    PIER_HIP(hipEventCreate(&c->offload_done));
+    c->device = dev;
+    return PIER_OK;
+}
+
+// A pointer handed over as "device memory": must be non-null, aligned to its
+// element, and lie with its whole extent inside one allocation of the current GPU.
+pier_status check_device_range(const void* ptr, int64_t numel, size_t elem, int device,
+                               const char* what, int tensor)
+{
+    if (numel == 0) return PIER_OK;
+    if (!ptr) return fail(PIER_ERR_INVALID_ARG, "%s[%d] is NULL", what, tensor);
+    if (reinterpret_cast<uintptr_t>(ptr) % elem)
+        return fail(PIER_ERR_ALIGNMENT, "%s[%d] is not aligned to %zu bytes", what, tensor, elem);
+    hipPointerAttribute_t at;
+    hipError_t e = hipPointerGetAttributes(&at, ptr);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PIER_ERR_INVALID_ARG, "%s[%d] is not memory known to HIP (%s)", what, tensor,
+                    hipGetErrorString(e));
+    }
+    if (at.type != hipMemoryTypeDevice && at.type != hipMemoryTypeManaged)
+        return fail(PIER_ERR_INVALID_ARG, "%s[%d] is not device memory", what, tensor);
+    if (at.type == hipMemoryTypeDevice && at.device != device)
+        return fail(PIER_ERR_INVALID_ARG, "%s[%d] lives on device %d, context on %d", what, tensor,
+                    at.device, device);
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    e = hipMemGetAddressRange(&base, &size, const_cast<void*>(ptr));
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PIER_ERR_INVALID_ARG, "%s[%d]: cannot query its allocation (%s)", what, tensor,
+                    hipGetErrorString(e));
+    }
+    const char* b = static_cast<const char*>(base);
+    const char* q = static_cast<const char*>(ptr);
+    if (q < b || q + static_cast<size_t>(numel) * elem > b + size)
+        return fail(PIER_ERR_INVALID_ARG, "%s[%d]: %lld elements do not fit its allocation", what,
+                    tensor, static_cast<long long>(numel));
+    return PIER_OK;
+}
+
+pier_status check_outer_hp(const pier_outer_hp* hp)
+{
+    if (!hp) return fail(PIER_ERR_INVALID_ARG, "hp is NULL");
+    if (hp->phase != PIER_PHASE_WARMUP && hp->phase != PIER_PHASE_PIER)
+        return fail(PIER_ERR_INVALID_ARG, "hp->phase is neither WARMUP nor PIER");
+    if (!std::isfinite(hp->mu) || !std::isfinite(hp->outer_lr))
+        return fail(PIER_ERR_INVALID_ARG, "hp->mu / hp->outer_lr is not finite");
+    return PIER_OK;
+}
+
+pier_status check_all_bound(const pier_ctx* c)
+{
+    for (int r = 0; r < c->n_replicas; ++r)
+        if (!c->rep_bound[r]) return fail(PIER_ERR_STATE, "replica %d is not bound", r);
+    return PIER_OK;
+}
+
+void free_plan(OffloadPlan& p)
+{
+    if (p.d_chunks) (void)hipFree(p.d_chunks);
+    for (hipEvent_t e : p.ev) (void)hipEventDestroy(e);
+    p.ev.clear();
+    p.d_chunks = nullptr;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pier_last_error(void) { return g_last_error.c_str(); }
+
+const char* pier_status_string(pier_status s)
+{
+    switch (s) {
+    case PIER_OK: return "PIER_OK";
+    case PIER_ERR_INVALID_ARG: return "PIER_ERR_INVALID_ARG";
+    case PIER_ERR_ALIGNMENT: return "PIER_ERR_ALIGNMENT";
+    case PIER_ERR_STATE: return "PIER_ERR_STATE";
+    case PIER_ERR_OOM: return "PIER_ERR_OOM";
+    case PIER_ERR_HIP: return "PIER_ERR_HIP";
+    }
+    return "PIER_ERR_UNKNOWN";
+}
+
+pier_status pier_ctx_create(pier_ctx** out, int n_tensors, const int64_t* numel, int n_replicas)
+{
+    if (!out) return fail(PIER_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (n_tensors < 1) return fail(PIER_ERR_INVALID_ARG, "n_tensors = %d, need >= 1", n_tensors);
+    if (!numel) return fail(PIER_ERR_INVALID_ARG, "numel is NULL");
+    if (n_replicas < 1 || n_replicas > PIER_MAX_REPLICAS)
+        return fail(PIER_ERR_INVALID_ARG, "n_replicas = %d, need 1..%d", n_replicas,
+                    PIER_MAX_REPLICAS);
+    pier_ctx* c = new (std::nothrow) pier_ctx;
+    if (!c) return fail(PIER_ERR_OOM, "out of host memory");
+    try {
+        c->n_tensors = n_tensors;
+        c->n_replicas = n_replicas;
+        c->numel.assign(numel, numel + n_tensors);
+        c->flat_start.assign(n_tensors + 1, 0);
+        for (int i = 0; i < n_tensors; ++i) {
+            if (numel[i] < 0) {
+                delete c;
+                return fail(PIER_ERR_INVALID_ARG, "numel[%d] = %lld is negative", i,
+                            static_cast<long long>(numel[i]));
+            }
+            if (numel[i] > INT64_MAX / 8 - c->flat_start[i]) {
+                delete c;
+                return fail(PIER_ERR_INVALID_ARG, "total element count overflows");
+            }
+            c->flat_start[i + 1] = c->flat_start[i] + numel[i];
+        }
+        c->N = c->flat_start[n_tensors];
+        c->h_rep.assign(static_cast<size_t>(n_replicas) * n_tensors, RepPtrs{});
+        c->rep_bound.assign(n_replicas, 0);
+        c->rep_bf16.assign(n_replicas, 0);
+        c->h_outer.assign(n_tensors, OuterPtrs{});
+        for (int i = 0; i < n_tensors; ++i) c->h_outer[i].flat_start = c->flat_start[i];
+    } catch (const std::bad_alloc&) {
+        delete c;
+        return fail(PIER_ERR_OOM, "out of host memory");
+    }
+    *out = c;
+    return PIER_OK;
+}
+
+pier_status pier_ctx_destroy(pier_ctx* c)
+{
+    if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
+    if (c->device >= 0) {
+        if (c->d_chunks) (void)hipFree(c->d_chunks);
+        if (c->d_rep) (void)hipFree(c->d_rep);
+        if (c->d_outer) (void)hipFree(c->d_outer);
+        for (auto& kv : c->plans) free_plan(kv.second);
+        if (c->offload_done) (void)hipEventDestroy(c->offload_done);
+    }
+    delete c;
+    return PIER_OK;
+}
+
+int64_t pier_ctx_numel(const pier_ctx* c) { return c ? c->N : -1; }
+
+pier_status pier_ctx_set_launch(pier_ctx* c, int64_t chunk_elems, int unroll, int max_grid,
+                                int nontemporal)
+{
+    if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
+    if (c->device >= 0) return fail(PIER_ERR_STATE, "launch shape must be set before the first bind");
+    if (chunk_elems != 0) {
+        if (chunk_elems < 1024 || chunk_elems % 1024 || chunk_elems > (1 << 30))
+            return fail(PIER_ERR_INVALID_ARG, "chunk_elems = %lld: need a multiple of 1024 in [1024, 2^30]",
+                        static_cast<long long>(chunk_elems));
+    }
+    if (unroll != 0 && unroll != 1 && unroll != 2 && unroll != 4)
+        return fail(PIER_ERR_INVALID_ARG, "unroll = %d: need 1, 2 or 4", unroll);
+    if (max_grid < 0) return fail(PIER_ERR_INVALID_ARG, "max_grid is negative");
+    if (nontemporal < -1 || nontemporal > 1)
+        return fail(PIER_ERR_INVALID_ARG, "nontemporal = %d: need 0, 1 or -1", nontemporal);
+    if (chunk_elems) c->chunk_elems = chunk_elems;
+    if (unroll) c->shape.unroll = unroll;
+    c->shape.max_grid = max_grid;
+    if (nontemporal >= 0) c->shape.nontemporal = nontemporal;
+    return PIER_OK;
+}
+
+pier_status pier_bind_replica(pier_ctx* c, int replica, float* const* p, float* const* m,
+                              float* const* v, const void* const* grad, int grad_is_bf16)
+{
+    if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
+    if (replica < 0 || replica >= c->n_replicas)
+        return fail(PIER_ERR_INVALID_ARG, "replica = %d, context has %d", replica, c->n_replicas);
+    if (!p || !m || !v || !grad) return fail(PIER_ERR_INVALID_ARG, "a pointer list is NULL");
+    pier_status st = ensure_device(c);
+    if (st != PIER_OK) return st;
+    const size_t gelem = grad_is_bf16 ? 2 : 4;
+    for (int i = 0; i < c->n_tensors; ++i) {
+        const int64_t n = c->numel[i];
+        if ((st = check_device_range(p[i], n, 4, c->device, "p", i)) != PIER_OK) return st;
+        if ((st = check_device_range(m[i], n, 4, c->device, "m", i)) != PIER_OK) return st;
+        if ((st = check_device_range(v[i], n, 4, c->device, "v", i)) != PIER_OK) return st;
+        if ((st = check_device_range(grad[i], n, gelem, c->device, "grad", i)) != PIER_OK) return st;
+    }
+    RepPtrs* row = c->h_rep.data() + static_cast<size_t>(replica) * c->n_tensors;
+    for (int i = 0; i < c->n_tensors; ++i) row[i] = RepPtrs{p[i], m[i], v[i], grad[i]};
+    PIER_HIP(hipMemcpy(c->d_rep + static_cast<size_t>(replica) * c->n_tensors, row,
+                       sizeof(RepPtrs) * c->n_tensors, hipMemcpyHostToDevice));
+    c->rep_bound[replica] = 1;
+    c->rep_bf16[replica] = grad_is_bf16 ? 1 : 0;
+    return PIER_OK;
+}
+
+pier_status pier_bind_outer(pier_ctx* c, pier_loc loc, float* const* anchor,
+                            float* const* momentum)
+{
+    if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
+    if (loc != PIER_LOC_DEVICE && loc != PIER_LOC_HOST_PINNED)
+        return fail(PIER_ERR_INVALID_ARG, "loc is neither DEVICE nor HOST_PINNED");
+    if (!anchor || !momentum) return fail(PIER_ERR_INVALID_ARG, "a pointer list is NULL");
+    pier_status st = ensure_device(c);
+    if (st != PIER_OK) return st;
+    if (loc == PIER_LOC_DEVICE) {
+        for (int i = 0; i < c->n_tensors; ++i) {
+            if ((st = check_device_range(anchor[i], c->numel[i], 4, c->device, "anchor", i)) != PIER_OK) return st;
+            if ((st = check_device_range(momentum[i], c->numel[i], 4, c->device, "momentum", i)) != PIER_OK) return st;
+        }
+        for (int i = 0; i < c->n_tensors; ++i) {
+            c->h_outer[i].a = anchor[i];
+            c->h_outer[i].M = momentum[i];
+        }
+        PIER_HIP(hipMemcpy(c->d_outer, c->h_outer.data(), sizeof(OuterPtrs) * c->n_tensors,
+                           hipMemcpyHostToDevice));
+        c->host_a = c->host_M = nullptr;
+    } else {
+        float* arr[2] = {anchor[0], momentum[0]};
+        const char* names[2] = {"anchor", "momentum"};
+        for (int k = 0; k < 2; ++k) {
+            if (c->N == 0) break;
+            if (!arr[k]) return fail(PIER_ERR_INVALID_ARG, "%s[0] is NULL", names[k]);
+            if (reinterpret_cast<uintptr_t>(arr[k]) % 4)
+                return fail(PIER_ERR_ALIGNMENT, "%s[0] is not aligned to 4 bytes", names[k]);
+            hipPointerAttribute_t at;
+            hipError_t e = hipPointerGetAttributes(&at, arr[k]);
+            if (e != hipSuccess || at.type != hipMemoryTypeHost) {
+                (void)hipGetLastError();
+                return fail(PIER_ERR_INVALID_ARG, "%s[0] is not pinned host memory", names[k]);
+            }
+        }
+        c->host_a = arr[0];
+        c->host_M = arr[1];
+    }
+    c->outer_loc = loc;
+    c->outer_bound = true;
+    return PIER_OK;
+}
+
+pier_status pier_inner_adamw(pier_ctx* c, int replica, const pier_adamw_hp* hp, void* hip_stream)
+{
+    if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
+    if (!hp) return fail(PIER_ERR_INVALID_ARG, "hp is NULL");
+    if (replica < 0 || replica >= c->n_replicas)
+        return fail(PIER_ERR_INVALID_ARG, "replica = %d, context has %d", replica, c->n_replicas);
+    if (!c->rep_bound[replica]) return fail(PIER_ERR_STATE, "replica %d is not bound", replica);
+    if (hp->step < 1) return fail(PIER_ERR_INVALID_ARG, "step = %lld, need >= 1", static_cast<long long>(hp->step));
+    if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) || !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f))
+        return fail(PIER_ERR_INVALID_ARG, "betas must lie in [0, 1)");
+    if (!std::isfinite(hp->lr) || !std::isfinite(hp->eps) || !std::isfinite(hp->weight_decay) ||
+        !std::isfinite(hp->grad_scale) || hp->eps < 0.0f)
+        return fail(PIER_ERR_INVALID_ARG, "lr / eps / weight_decay / grad_scale not finite, or eps < 0");
+    pier_status st = ensure_device(c);
+    if (st != PIER_OK) return st;
+
+    AdamwScalars s;
+    s.lr = hp->lr;
+    s.beta1 = hp->beta1;
+    s.beta2 = hp->beta2;
+    s.om1 = 1.0f - hp->beta1;
+    s.om2 = 1.0f - hp->beta2;
+    s.eps = hp->eps;
+    s.wd = hp->weight_decay;
+    // bias corrections 1 - beta^t: formed in double, applied in fp32
+    s.bc1 = static_cast<float>(1.0 - std::pow(static_cast<double>(hp->beta1), static_cast<double>(hp->step)));
+    s.bc2 = static_cast<float>(1.0 - std::pow(static_cast<double>(hp->beta2), static_cast<double>(hp->step)));
+    s.grad_scale = hp->grad_scale;
+    PIER_HIP(launch_adamw(c->d_chunks, c->n_chunks,
+                          c->d_rep + static_cast<size_t>(replica) * c->n_tensors,
+                          c->rep_bf16[replica] != 0, s, c->shape, static_cast<hipStream_t>(hip_stream)));
+    return PIER_OK;
+}
+
+pier_status pier_outer_step(pier_ctx* c, const pier_outer_hp* hp, void* hip_stream)
+{
+    if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
+    pier_status st = check_outer_hp(hp);
+    if (st != PIER_OK) return st;
+    if ((st = check_all_bound(c)) != PIER_OK) return st;
+    if (!c->outer_bound || c->outer_loc != PIER_LOC_DEVICE)
+        return fail(PIER_ERR_STATE, "anchor and momentum are not bound as device tensors");
+    if ((st = ensure_device(c)) != PIER_OK) return st;
+    PIER_HIP(launch_outer(c->d_chunks, c->n_chunks, c->d_rep, c->n_tensors, c->n_replicas, c->d_outer,
+                          nullptr, nullptr, 0, hp->mu, hp->outer_lr, hp->phase == PIER_PHASE_PIER,
+                          c->shape, static_cast<hipStream_t>(hip_stream)));
+    return PIER_OK;
+}
+
+pier_status pier_offload_workspace_bytes(const pier_ctx* c, size_t chunk_bytes, size_t* out)
+{
+    if (!c || !out) return fail(PIER_ERR_INVALID_ARG, "ctx or out is NULL");
+    if (chunk_bytes < 16 || chunk_bytes % 16)
+        return fail(PIER_ERR_INVALID_ARG, "chunk_bytes must be a positive multiple of 16");
+    const size_t total = static_cast<size_t>(c->N) * 4;
+    const size_t piece = std::min(chunk_bytes, std::max<size_t>(16, (total + 15) / 16 * 16));
+    const size_t n_pieces = (total + piece - 1) / piece;
+    *out = 2 * piece * std::max<size_t>(1, std::min<size_t>(3, n_pieces));
+    return PIER_OK;
+}
+
+pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chunk_bytes,
+                                void* workspace, size_t workspace_bytes, void* compute_stream,
+                                void* h2d_stream, void* d2h_stream, pier_offload_stats* stats)
+{
+    if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
+    pier_status st = check_outer_hp(hp);
+    if (st != PIER_OK) return st;
+    if ((st = check_all_bound(c)) != PIER_OK) return st;
+    if (!c->outer_bound || c->outer_loc != PIER_LOC_HOST_PINNED)
+        return fail(PIER_ERR_STATE, "anchor and momentum are not bound as pinned host arrays");
+    if (chunk_bytes < 16 || chunk_bytes % 16)
+        return fail(PIER_ERR_INVALID_ARG, "chunk_bytes must be a positive multiple of 16");
+    if ((st = ensure_device(c)) != PIER_OK) return st;
+    if (stats) std::memset(stats, 0, sizeof *stats);
+    if (c->N == 0) return PIER_OK;
+
+    const size_t total = static_cast<size_t>(c->N) * 4;
+    const size_t piece_bytes = std::min(chunk_bytes, (total + 15) / 16 * 16);
+    const int64_t piece_elems = static_cast<int64_t>(piece_bytes / 4);
+    const int n_pieces = static_cast<int>((c->N + piece_elems - 1) / piece_elems);
+    const int n_slots = static_cast<int>(std::min<size_t>(std::min<size_t>(4, n_pieces),
+                                                          workspace_bytes / (2 * piece_bytes)));
+    if (n_slots < 1)
+        return fail(PIER_ERR_INVALID_ARG, "workspace of %zu bytes holds no staging slot of 2 x %zu bytes",
+                    workspace_bytes, piece_bytes);
+    if ((st = check_device_range(workspace, static_cast<int64_t>(2 * piece_bytes) * n_slots, 1,
+                                 c->device, "workspace", 0)) != PIER_OK) return st;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16)
+        return fail(PIER_ERR_ALIGNMENT, "workspace is not aligned to 16 bytes");
+
+    OffloadPlan& plan = c->plans[piece_bytes];
+    if (plan.piece_elems == 0) {
+        std::vector<Chunk> chunks;
+        plan.piece_lo.clear();
+        plan.chunk_begin.clear();
+        for (int k = 0; k < n_pieces; ++k) {
+            const int64_t lo = k * piece_elems, hi = std::min<int64_t>(c->N, lo + piece_elems);
+            plan.piece_lo.push_back(lo);
+            plan.chunk_begin.push_back(static_cast<int>(chunks.size()));
+            build_chunks(c, lo, hi, chunks);
+        }
+        plan.piece_lo.push_back(c->N);
+        plan.chunk_begin.push_back(static_cast<int>(chunks.size()));
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&plan.d_chunks), sizeof(Chunk) * chunks.size());
+        if (e == hipSuccess)
+            e = hipMemcpy(plan.d_chunks, chunks.data(), sizeof(Chunk) * chunks.size(), hipMemcpyHostToDevice);
+        for (int i = 0; e == hipSuccess && i < 6 * n_pieces; ++i) {
+            hipEvent_t ev = nullptr;
+            e = hipEventCreate(&ev);
+            if (e == hipSuccess) plan.ev.push_back(ev);
+        }
+        if (e != hipSuccess) {
+            free_plan(plan);
+            c->plans.erase(piece_bytes);
+            return fail(e == hipErrorOutOfMemory ? PIER_ERR_OOM : PIER_ERR_HIP, "building the offload plan: %s",
+                        hipGetErrorString(e));
+        }
+        plan.piece_elems = piece_elems;
+    }
+
+    hipStream_t sc = static_cast<hipStream_t>(compute_stream);
+    hipStream_t sin = static_cast<hipStream_t>(h2d_stream);
+    hipStream_t sout = static_cast<hipStream_t>(d2h_stream);
+    char* ws = static_cast<char*>(workspace);
+    auto EV = [&](int k, int which) { return plan.ev[static_cast<size_t>(k) * 6 + which]; };
+    enum { H2D_B, H2D_E, KER_B, KER_E, D2H_B, D2H_E };
+
+    // the host arrays and the staging slots may still be in use by the previous call
+    if (c->offload_done_valid) PIER_HIP(hipStreamWaitEvent(sin, c->offload_done, 0));
+
+    for (int k = 0; k < n_pieces; ++k) {
+        const int slot = k % n_slots;
+        float* sa = reinterpret_cast<float*>(ws + static_cast<size_t>(slot) * 2 * piece_bytes);
+        float* sM = reinterpret_cast<float*>(ws + static_cast<size_t>(slot) * 2 * piece_bytes + piece_bytes);
+        const int64_t lo = plan.piece_lo[k], hi = plan.piece_lo[k + 1];
+        const size_t bytes = static_cast<size_t>(hi - lo) * 4;
+
+        // stage 1: reload the previous model and the momentum of this piece
+        if (k >= n_slots) PIER_HIP(hipStreamWaitEvent(sin, EV(k - n_slots, D2H_E), 0));
+        PIER_HIP(hipEventRecord(EV(k, H2D_B), sin));
+        PIER_HIP(hipMemcpyAsync(sa, c->host_a + lo, bytes, hipMemcpyHostToDevice, sin));
+        PIER_HIP(hipMemcpyAsync(sM, c->host_M + lo, bytes, hipMemcpyHostToDevice, sin));
+        PIER_HIP(hipEventRecord(EV(k, H2D_E), sin));
+
+        // stage 2: the outer step on this piece
+        PIER_HIP(hipStreamWaitEvent(sc, EV(k, H2D_E), 0));
+        PIER_HIP(hipEventRecord(EV(k, KER_B), sc));
+        PIER_HIP(launch_outer(plan.d_chunks + plan.chunk_begin[k],
+                              plan.chunk_begin[k + 1] - plan.chunk_begin[k], c->d_rep, c->n_tensors,
+                              c->n_replicas, c->d_outer, sa, sM, lo, hp->mu, hp->outer_lr,
+                              hp->phase == PIER_PHASE_PIER, c->shape, sc));
+        PIER_HIP(hipEventRecord(EV(k, KER_E), sc));
+
+        // stage 3: offload the new model and momentum of this piece
+        PIER_HIP(hipStreamWaitEvent(sout, EV(k, KER_E), 0));
+        PIER_HIP(hipEventRecord(EV(k, D2H_B), sout));
+        PIER_HIP(hipMemcpyAsync(c->host_a + lo, sa, bytes, hipMemcpyDeviceToHost, sout));
+        PIER_HIP(hipMemcpyAsync(c->host_M + lo, sM, bytes, hipMemcpyDeviceToHost, sout));
+        PIER_HIP(hipEventRecord(EV(k, D2H_E), sout));
+    }
+    PIER_HIP(hipEventRecord(c->offload_done, sout));
+    c->offload_done_valid = true;
+    PIER_HIP(hipStreamWaitEvent(sc, c->offload_done, 0));
+
+    if (stats) {
+        PIER_HIP(hipEventSynchronize(c->offload_done));
+        stats->n_pieces = n_pieces;
+        stats->n_slots = n_slots;
+        stats->h2d_bytes = stats->d2h_bytes = 2.0 * static_cast<double>(total);
+        for (int k = 0; k < n_pieces; ++k) {
+            float ms = 0.f;
+            PIER_HIP(hipEventElapsedTime(&ms, EV(k, H2D_B), EV(k, H2D_E)));
+            stats->h2d_ms += ms;
+            PIER_HIP(hipEventElapsedTime(&ms, EV(k, KER_B), EV(k, KER_E)));
+            stats->kernel_ms += ms;
+            PIER_HIP(hipEventElapsedTime(&ms, EV(k, D2H_B), EV(k, D2H_E)));
+            stats->d2h_ms += ms;
+        }
+        float wall = 0.f;
+        PIER_HIP(hipEventElapsedTime(&wall, EV(0, H2D_B), EV(n_pieces - 1, D2H_E)));
+        stats->wall_ms = wall;
+    }
+    return PIER_OK;
+}
+
+float pier_mu_schedule(int64_t t, int64_t T)
+{
+    if (10 * t >= T && 100 * t < 15 * T) return 0.99f;
+    if (100 * t >= 15 * T && 10 * t < 2 * T) return 0.95f;
+    return 0.9f;
+}
+
+float pier_outer_lr_schedule(int64_t t, int64_t T)
+{
+    if (10 * t < T) return 0.0f;
+    if (10 * t < 2 * T) return static_cast<float>(static_cast<double>(10 * t - T) / static_cast<double>(T));
+    if (10 * t < 8 * T) return 1.1f;
+    return 0.9f;
+}
+
+pier_status pier_outer_schedule(int64_t t, int64_t T, pier_outer_hp* out)
+{
+    if (!out) return fail(PIER_ERR_INVALID_ARG, "out is NULL");
+    if (T < 1 || t < 1 || t > T)
+        return fail(PIER_ERR_INVALID_ARG, "need 1 <= t <= T (t = %lld, T = %lld)", static_cast<long long>(t),
+                    static_cast<long long>(T));
+    if (10 * t <= T) {
+        out->phase = PIER_PHASE_WARMUP;
+        out->mu = 0.9f;
+        out->outer_lr = 0.0f;
+    } else {
+        out->phase = PIER_PHASE_PIER;
+        out->mu = pier_mu_schedule(t, T);
+        out->outer_lr = pier_outer_lr_schedule(t, T);
+    }
+    return PIER_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,499 @@
+// HIP kernels of libpier for gfx950 (MI355X): the fused multi-tensor inner AdamW
+// step and the fused outer step of Pier's two-level optimizer.
+//
+// Both kernels are elementwise streams bound by HBM bandwidth, so the design is:
+//   * one workgroup of 4 wavefronts per chunk of a tensor (chunk table in device
+//     memory, read through the scalar unit because the index is wave-uniform);
+//   * 128-bit loads/stores, lane i of a wavefront touching vector i of a 1 KiB run,
+//     so every wave-level access is one fully coalesced 1 KiB burst per stream;
+//   * all loads of a tile (UNROLL vectors x every stream) are issued before the
+//     first use, so each lane keeps UNROLL x streams 16-byte requests in flight;
+//   * every buffer is read once and written once per launch; nothing is staged in
+//     LDS because no element is shared between lanes (the sum over the G replicas
+//     is a per-lane register reduction: replica g's element i lives at the same
+//     index i of a different stream);
+//   * no MFMA: there is no contraction anywhere on this path.
+// Arithmetic is written in the order the update rules are stated, one fp32
+// operation per operator, with FMA contraction switched off and correctly rounded
+// division and square root, so results do not depend on how the compiler schedules
+// the expression.
+#include "pier_internal.h"
+
+namespace pier {
+
+typedef float vfloat4 __attribute__((ext_vector_type(4)));
+typedef unsigned short vushort4 __attribute__((ext_vector_type(4)));
+
+// Every pointer the kernels follow comes out of a table in memory, so the compiler
+// cannot tell it addresses global memory and would fall back to flat instructions.
+// All accesses therefore go through these helpers, which cast to the global address
+// space (global_load / global_store) and apply the streaming hint.
+#define PIER_GLOBAL __attribute__((address_space(1)))
+
+template <bool NT, typename T>
+__device__ __forceinline__ T ld(const T* p)
+{
+    const PIER_GLOBAL T* q = (const PIER_GLOBAL T*)p;
+    if constexpr (NT) return __builtin_nontemporal_load(q);
+    else return *q;
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ void st(T* p, T x)
+{
+    PIER_GLOBAL T* q = (PIER_GLOBAL T*)p;
+    if constexpr (NT) __builtin_nontemporal_store(x, q);
+    else *q = x;
+}
+
+__device__ __forceinline__ float bf16_to_f32(unsigned short h)
+{
+    return __uint_as_float(static_cast<unsigned int>(h) << 16);
+}
+
+// ------------------------------------------------------------------ inner AdamW
+//
+// AdamW with decoupled weight decay and bias correction (the inner optimizer of
+// Algorithm 1 / Algorithm 2, hyper-parameters of Table I).
+__device__ __forceinline__ void adamw_elem(float& p, float& m, float& v, float g,
+                                           const AdamwScalars& s)
+{
+#pragma clang fp contract(off)
+    g = g * s.grad_scale;
+    const float mn = s.beta1 * m + s.om1 * g;
+    const float vn = s.beta2 * v + (s.om2 * g) * g;
+    const float mh = mn / s.bc1;
+    const float vh = vn / s.bc2;
+    const float u = mh / (sqrtf(vh) + s.eps) + s.wd * p;
+    p = p - s.lr * u;
+    m = mn;
+    v = vn;
+}
+
+template <bool BF16>
+struct GradVec;
+template <>
+struct GradVec<false> {
+    typedef vfloat4 type;
+    static __device__ __forceinline__ vfloat4 widen(vfloat4 x) { return x; }
+};
+template <>
+struct GradVec<true> {
+    typedef vushort4 type;
+    static __device__ __forceinline__ vfloat4 widen(vushort4 x)
+    {
+        vfloat4 r;
+        r.x = bf16_to_f32(x.x);
+        r.y = bf16_to_f32(x.y);
+        r.z = bf16_to_f32(x.z);
+        r.w = bf16_to_f32(x.w);
+        return r;
+    }
+};
+
+__device__ __forceinline__ void adamw_vec(vfloat4& P, vfloat4& M, vfloat4& V, const vfloat4& G,
+                                          const AdamwScalars& s)
+{
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float p = P[k], m = M[k], v = V[k];
+        adamw_elem(p, m, v, G[k], s);
+        P[k] = p;
+        M[k] = m;
+        V[k] = v;
+    }
+}
+
+template <bool BF16, typename GS>
+__device__ __forceinline__ void adamw_scalar(float* p, float* m, float* v, const GS* g,
+                                             const AdamwScalars& s)
+{
+    float pi = ld<false>(p), mi = ld<false>(m), vi = ld<false>(v), gi;
+    if constexpr (BF16) gi = bf16_to_f32(ld<false>(g)); else gi = ld<false>(g);
+    adamw_elem(pi, mi, vi, gi, s);
+    st<false>(p, pi);
+    st<false>(m, mi);
+    st<false>(v, vi);
+}
+
+template <int UNROLL, bool BF16, bool NT>
+__global__ __launch_bounds__(kBlock) void adamw_kernel(const Chunk* __restrict__ chunks,
+                                                       int n_chunks,
+                                                       const RepPtrs* __restrict__ tab,
+                                                       AdamwScalars s)
+{
+    typedef typename GradVec<BF16>::type gvec;
+    typedef typename std::conditional<BF16, unsigned short, float>::type gscalar;
+    const int tid = threadIdx.x;
+    constexpr int kTile = kBlock * UNROLL;  // vectors per tile
+
+    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const Chunk ch = chunks[c];
+        const RepPtrs t = tab[ch.tensor];
+        float* __restrict__ p = t.p + ch.off;
+        float* __restrict__ m = t.m + ch.off;
+        float* __restrict__ v = t.v + ch.off;
+        const gscalar* __restrict__ g = static_cast<const gscalar*>(t.g) + ch.off;
+        const int len = ch.len;
+
+        const uintptr_t mis = (reinterpret_cast<uintptr_t>(p) | reinterpret_cast<uintptr_t>(m) |
+                               reinterpret_cast<uintptr_t>(v)) & 15u;
+        const uintptr_t gmis = reinterpret_cast<uintptr_t>(g) & (sizeof(gvec) - 1);
+        if ((mis | gmis) == 0) {
+            vfloat4* p4 = reinterpret_cast<vfloat4*>(p);
+            vfloat4* m4 = reinterpret_cast<vfloat4*>(m);
+            vfloat4* v4 = reinterpret_cast<vfloat4*>(v);
+            const gvec* g4 = reinterpret_cast<const gvec*>(g);
+            const int n4 = len >> 2;
+            int base = 0;
+            for (; base + kTile <= n4; base += kTile) {
+                vfloat4 P[UNROLL], M[UNROLL], V[UNROLL];
+                gvec Gr[UNROLL];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const int i = base + u * kBlock + tid;
+                    P[u] = ld<NT>(p4 + i);
+                    M[u] = ld<NT>(m4 + i);
+                    V[u] = ld<NT>(v4 + i);
+                    Gr[u] = ld<NT>(g4 + i);
+                }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const int i = base + u * kBlock + tid;
+                    adamw_vec(P[u], M[u], V[u], GradVec<BF16>::widen(Gr[u]), s);
+                    st<NT>(p4 + i, P[u]);
+                    st<NT>(m4 + i, M[u]);
+                    st<NT>(v4 + i, V[u]);
+                }
+            }
+            // ragged last tile of the chunk
+            for (int i = base + tid; i < n4; i += kBlock) {
+                vfloat4 P = ld<NT>(p4 + i), M = ld<NT>(m4 + i), V = ld<NT>(v4 + i);
+                const gvec Gr = ld<NT>(g4 + i);
+                adamw_vec(P, M, V, GradVec<BF16>::widen(Gr), s);
+                st<NT>(p4 + i, P);
+                st<NT>(m4 + i, M);
+                st<NT>(v4 + i, V);
+            }
+            // up to three elements past the last whole vector
+            const int i = (n4 << 2) + tid;
+            if (i < len) adamw_scalar<BF16>(p + i, m + i, v + i, g + i, s);
+        } else {
+            for (int i = tid; i < len; i += kBlock) adamw_scalar<BF16>(p + i, m + i, v + i, g + i, s);
+        }
+    }
+}
+
+static int grid_for(int n_chunks, const LaunchShape& shape)
+{
+    if (shape.max_grid > 0 && n_chunks > shape.max_grid) return shape.max_grid;
+    return n_chunks;
+}
+
+template <int U, bool BF16>
+static void adamw_dispatch_nt(int grid, const Chunk* chunks, int n_chunks, const RepPtrs* tab,
+                              const AdamwScalars& s, bool nt, hipStream_t stream)
+{
+    if (nt) hipLaunchKernelGGL((adamw_kernel<U, BF16, true>), dim3(grid), dim3(kBlock), 0, stream,
+                               chunks, n_chunks, tab, s);
+    else hipLaunchKernelGGL((adamw_kernel<U, BF16, false>), dim3(grid), dim3(kBlock), 0, stream,
+                            chunks, n_chunks, tab, s);
+}
+
+template <bool BF16>
+static void adamw_dispatch_u(int grid, const Chunk* chunks, int n_chunks, const RepPtrs* tab,
+                             const AdamwScalars& s, const LaunchShape& shape, hipStream_t stream)
+{
+    const bool nt = shape.nontemporal != 0;
+    switch (shape.unroll) {
+    case 1: adamw_dispatch_nt<1, BF16>(grid, chunks, n_chunks, tab, s, nt, stream); break;
+    case 2: adamw_dispatch_nt<2, BF16>(grid, chunks, n_chunks, tab, s, nt, stream); break;
+    default: adamw_dispatch_nt<4, BF16>(grid, chunks, n_chunks, tab, s, nt, stream); break;
+    }
+}
+
+hipError_t launch_adamw(const Chunk* chunks, int n_chunks, const RepPtrs* tab, bool grad_bf16,
+                        const AdamwScalars& s, const LaunchShape& shape, hipStream_t stream)
+{
+    if (n_chunks <= 0) return hipSuccess;
+    const int grid = grid_for(n_chunks, shape);
+    if (grad_bf16) adamw_dispatch_u<true>(grid, chunks, n_chunks, tab, s, shape, stream);
+    else adamw_dispatch_u<false>(grid, chunks, n_chunks, tab, s, shape, stream);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ outer step
+//
+// Algorithm 2, synchronisation branch, for one element held by G groups:
+//   delta = (1/G) sum_g (theta_g - anchor);  M = mu M + delta;
+//   Pier:   theta = anchor + lr (mu M + delta), written to the anchor and to all groups;
+//   warmup: (Algorithm 1) momentum only; the anchor takes the current model, which
+//           is the mean of the (identical) groups; groups untouched.
+// The sum over groups runs g = 0 .. G-1 in that order.
+template <int G, bool PIER>
+__device__ __forceinline__ void outer_elem(float (&th)[G], float& a, float& M, float mu, float lr,
+                                           float invG)
+{
+#pragma clang fp contract(off)
+    float s = 0.0f;
+#pragma unroll
+    for (int g = 0; g < G; ++g) s = s + (th[g] - a);
+    const float d = s * invG;
+    const float Mn = mu * M + d;
+    M = Mn;
+    if constexpr (PIER) {
+        const float x = a + lr * (mu * Mn + d);
+        a = x;
+#pragma unroll
+        for (int g = 0; g < G; ++g) th[g] = x;
+    } else {
+        float s2 = 0.0f;
+#pragma unroll
+        for (int g = 0; g < G; ++g) s2 = s2 + th[g];
+        a = s2 * invG;
+    }
+}
+
+template <int G, bool PIER>
+__device__ __forceinline__ void outer_vec(vfloat4 (&TH)[G], vfloat4& A, vfloat4& M, float mu,
+                                          float lr, float invG)
+{
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float th[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) th[g] = TH[g][k];
+        float a = A[k], mm = M[k];
+        outer_elem<G, PIER>(th, a, mm, mu, lr, invG);
+        A[k] = a;
+        M[k] = mm;
+        if constexpr (PIER) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) TH[g][k] = th[g];
+        }
+    }
+}
+
+template <int G, bool PIER>
+__device__ __forceinline__ void outer_scalar(float* const (&th)[G], float* a, float* M, int i,
+                                             float mu, float lr, float invG)
+{
+    float t[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) t[g] = ld<false>(th[g] + i);
+    float av = ld<false>(a + i), mv = ld<false>(M + i);
+    outer_elem<G, PIER>(t, av, mv, mu, lr, invG);
+    st<false>(a + i, av);
+    st<false>(M + i, mv);
+    if constexpr (PIER) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) st<false>(th[g] + i, t[g]);
+    }
+}
+
+struct OuterArgs {
+    const Chunk* chunks;
+    const RepPtrs* rep_tab;
+    const OuterPtrs* otab;
+    float* flat_a;
+    float* flat_M;
+    int64_t flat_lo;
+    int n_chunks;
+    int n_tensors;
+    int G;
+    float mu, lr, invG;
+};
+
+template <int G, int UNROLL, bool FLAT, bool PIER, bool NT>
+__global__ __launch_bounds__(kBlock) void outer_kernel(OuterArgs A)
+{
+    const int tid = threadIdx.x;
+    constexpr int kTile = kBlock * UNROLL;
+
+    for (int c = blockIdx.x; c < A.n_chunks; c += gridDim.x) {
+        const Chunk ch = A.chunks[c];
+        const OuterPtrs ot = A.otab[ch.tensor];
+        float* __restrict__ a;
+        float* __restrict__ M;
+        if constexpr (FLAT) {
+            const int64_t e = ot.flat_start + ch.off - A.flat_lo;
+            a = A.flat_a + e;
+            M = A.flat_M + e;
+        } else {
+            a = ot.a + ch.off;
+            M = ot.M + ch.off;
+        }
+        float* th[G];
+        uintptr_t mis = reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(M);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            th[g] = A.rep_tab[static_cast<int64_t>(g) * A.n_tensors + ch.tensor].p + ch.off;
+            mis |= reinterpret_cast<uintptr_t>(th[g]);
+        }
+        const int len = ch.len;
+
+        if ((mis & 15u) == 0) {
+            vfloat4* a4 = reinterpret_cast<vfloat4*>(a);
+            vfloat4* M4 = reinterpret_cast<vfloat4*>(M);
+            const int n4 = len >> 2;
+            int base = 0;
+            for (; base + kTile <= n4; base += kTile) {
+                vfloat4 TH[UNROLL][G], Av[UNROLL], Mv[UNROLL];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const int i = base + u * kBlock + tid;
+                    Av[u] = ld<NT>(a4 + i);
+                    Mv[u] = ld<NT>(M4 + i);
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        TH[u][g] = ld<NT>(reinterpret_cast<const vfloat4*>(th[g]) + i);
+                }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const int i = base + u * kBlock + tid;
+                    outer_vec<G, PIER>(TH[u], Av[u], Mv[u], A.mu, A.lr, A.invG);
+                    st<NT>(a4 + i, Av[u]);
+                    st<NT>(M4 + i, Mv[u]);
+                    if constexpr (PIER) {
+#pragma unroll
+                        for (int g = 0; g < G; ++g)
+                            st<NT>(reinterpret_cast<vfloat4*>(th[g]) + i, TH[u][g]);
+                    }
+                }
+            }
+            for (int i = base + tid; i < n4; i += kBlock) {
+                vfloat4 TH[G], Av = ld<NT>(a4 + i), Mv = ld<NT>(M4 + i);
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    TH[g] = ld<NT>(reinterpret_cast<const vfloat4*>(th[g]) + i);
+                outer_vec<G, PIER>(TH, Av, Mv, A.mu, A.lr, A.invG);
+                st<NT>(a4 + i, Av);
+                st<NT>(M4 + i, Mv);
+                if constexpr (PIER) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) st<NT>(reinterpret_cast<vfloat4*>(th[g]) + i, TH[g]);
+                }
+            }
+            const int i = (n4 << 2) + tid;
+            if (i < len) outer_scalar<G, PIER>(th, a, M, i, A.mu, A.lr, A.invG);
+        } else {
+            for (int i = tid; i < len; i += kBlock) outer_scalar<G, PIER>(th, a, M, i, A.mu, A.lr, A.invG);
+        }
+    }
+}
+
+// Any number of groups: the replicas are walked in a run-time loop (same order,
+// same arithmetic), one element per lane.  Covers the group counts without a
+// specialised kernel.
+template <bool FLAT, bool PIER>
+__global__ __launch_bounds__(kBlock) void outer_kernel_anyG(OuterArgs A)
+{
+#pragma clang fp contract(off)
+    const int tid = threadIdx.x;
+    for (int c = blockIdx.x; c < A.n_chunks; c += gridDim.x) {
+        const Chunk ch = A.chunks[c];
+        const OuterPtrs ot = A.otab[ch.tensor];
+        float* __restrict__ a;
+        float* __restrict__ M;
+        if constexpr (FLAT) {
+            const int64_t e = ot.flat_start + ch.off - A.flat_lo;
+            a = A.flat_a + e;
+            M = A.flat_M + e;
+        } else {
+            a = ot.a + ch.off;
+            M = ot.M + ch.off;
+        }
+        const RepPtrs* rt = A.rep_tab + ch.tensor;
+        for (int i = tid; i < ch.len; i += kBlock) {
+            const float av = ld<false>(a + i);
+            float s = 0.0f, s2 = 0.0f;
+            for (int g = 0; g < A.G; ++g) {
+                const float t = ld<false>(rt[static_cast<int64_t>(g) * A.n_tensors].p + ch.off + i);
+                s = s + (t - av);
+                s2 = s2 + t;
+            }
+            const float d = s * A.invG;
+            const float Mn = A.mu * ld<false>(M + i) + d;
+            st<false>(M + i, Mn);
+            if constexpr (PIER) {
+                const float x = av + A.lr * (A.mu * Mn + d);
+                st<false>(a + i, x);
+                for (int g = 0; g < A.G; ++g)
+                    st<false>(rt[static_cast<int64_t>(g) * A.n_tensors].p + ch.off + i, x);
+            } else {
+                st<false>(a + i, s2 * A.invG);
+            }
+        }
+    }
+}
+
+template <int G, int U, bool FLAT, bool PIER>
+static void outer_dispatch_nt(int grid, const OuterArgs& A, bool nt, hipStream_t stream)
+{
+    if (nt) hipLaunchKernelGGL((outer_kernel<G, U, FLAT, PIER, true>), dim3(grid), dim3(kBlock), 0, stream, A);
+    else hipLaunchKernelGGL((outer_kernel<G, U, FLAT, PIER, false>), dim3(grid), dim3(kBlock), 0, stream, A);
+}
+
+template <int G, bool FLAT, bool PIER>
+static void outer_dispatch_u(int grid, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
+{
+    const bool nt = shape.nontemporal != 0;
+    // lanes keep (G + 2) * unroll 16-byte loads in flight; cap the product
+    int u = shape.unroll;
+    while (u > 1 && (G + 2) * u > 20) u >>= 1;
+    switch (u) {
+    case 1: outer_dispatch_nt<G, 1, FLAT, PIER>(grid, A, nt, stream); break;
+    case 2: outer_dispatch_nt<G, 2, FLAT, PIER>(grid, A, nt, stream); break;
+    default:
+        if constexpr ((G + 2) * 4 <= 20) outer_dispatch_nt<G, 4, FLAT, PIER>(grid, A, nt, stream);
+        else outer_dispatch_nt<G, 2, FLAT, PIER>(grid, A, nt, stream);
+        break;
+    }
+}
+
+template <bool FLAT, bool PIER>
+static void outer_dispatch_g(int grid, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
+{
+    switch (A.G) {
+    case 1: outer_dispatch_u<1, FLAT, PIER>(grid, A, shape, stream); break;
+    case 2: outer_dispatch_u<2, FLAT, PIER>(grid, A, shape, stream); break;
+    case 4: outer_dispatch_u<4, FLAT, PIER>(grid, A, shape, stream); break;
+    case 8: outer_dispatch_u<8, FLAT, PIER>(grid, A, shape, stream); break;
+    default:
+        hipLaunchKernelGGL((outer_kernel_anyG<FLAT, PIER>), dim3(grid), dim3(kBlock), 0, stream, A);
+        break;
+    }
+}
+
+hipError_t launch_outer(const Chunk* chunks, int n_chunks, const RepPtrs* rep_tab, int n_tensors,
+                        int G, const OuterPtrs* otab, float* flat_a, float* flat_M,
+                        int64_t flat_lo, float mu, float lr, bool pier_phase,
+                        const LaunchShape& shape, hipStream_t stream)
+{
+    if (n_chunks <= 0) return hipSuccess;
+    OuterArgs A;
+    A.chunks = chunks;
+    A.rep_tab = rep_tab;
+    A.otab = otab;
+    A.flat_a = flat_a;
+    A.flat_M = flat_M;
+    A.flat_lo = flat_lo;
+    A.n_chunks = n_chunks;
+    A.n_tensors = n_tensors;
+    A.G = G;
+    A.mu = mu;
+    A.lr = lr;
+    A.invG = 1.0f / static_cast<float>(G);
+    const int grid = grid_for(n_chunks, shape);
+    const bool flat = flat_a != nullptr;
+    if (flat) {
+        if (pier_phase) outer_dispatch_g<true, true>(grid, A, shape, stream);
+        else outer_dispatch_g<true, false>(grid, A, shape, stream);
+    } else {
+        if (pier_phase) outer_dispatch_g<false, true>(grid, A, shape, stream);
+        else outer_dispatch_g<false, false>(grid, A, shape, stream);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace pier

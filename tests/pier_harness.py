@@ -1,0 +1,192 @@
+"""GPU-vs-oracle parity harness.
+
+Drives the HIP library through the Python binding on device buffers while the CPU
+oracle follows the same update sequence on a sample of element indices (all of them
+for small cases).  Gradients are synthesised on the device by pier_inputs and the
+oracle reads its sample of each gradient back, so both sides consume identical bits.
+"""
+import numpy as np
+import torch
+
+import paper_2511_17849_amd as pier
+from oracle import pier_oracle as O
+from pier_inputs import device as dev
+from pier_inputs import shapes
+
+
+def tol_ok(got, ref):
+    """The parity bar: |err| <= 1e-6 * max(1, |x|) per fp32 element."""
+    got = got.astype(np.float64)
+    ref64 = ref.astype(np.float64)
+    return np.abs(got - ref64) <= 1e-6 * np.maximum(1.0, np.abs(ref64))
+
+
+def rel_ok(got, ref, rel=1e-5, floor=1e-12):
+    """Self-imposed bar for the small-magnitude state (m, v, M), where the absolute
+    bar is vacuous: relative 1e-5 with a floor far below the values' scale."""
+    got = got.astype(np.float64)
+    ref64 = ref.astype(np.float64)
+    return np.abs(got - ref64) <= rel * np.abs(ref64) + floor
+
+
+def sample_indices(numels, n_strided=1 << 16, chunk=16384, piece=None, pad=0):
+    """Deterministic sample of flat element indices: a strided sweep, the first and
+    last 8 elements of every tensor, and +-8 around every chunk (and piece) boundary
+    near the start of each tensor.  Indices address the padded flat buffer."""
+    starts, off = [], 0
+    for n in numels:
+        starts.append(off)
+        off += n + pad
+    N = sum(numels)
+    idx = []
+    for s, n in zip(starts, numels):
+        if n == 0:
+            continue
+        e = np.arange(min(8, n))
+        idx += [s + e, s + n - 1 - e]
+        for b in (chunk, 2 * chunk, (n // chunk) * chunk):
+            if 0 < b < n:
+                w = np.arange(max(0, b - 8), min(n, b + 8))
+                idx.append(s + w)
+    if piece and pad == 0:
+        for b in range(piece, N, piece):
+            idx.append(np.arange(max(0, b - 8), min(N, b + 8)))
+    if pad == 0 and N > 0:
+        stride = max(1, N // n_strided)
+        idx.append(np.arange(0, N, stride)[:n_strided + 8] + 0)
+    else:
+        for s, n in zip(starts, numels):
+            k = max(1, n_strided * n // max(N, 1))
+            if n:
+                idx.append(s + np.unique(np.linspace(0, n - 1, k).astype(np.int64)))
+    out = np.unique(np.concatenate([np.asarray(i, dtype=np.int64) for i in idx]))
+    return out
+
+
+class Run:
+    """One workload on the device plus its sampled oracle shadow."""
+
+    def __init__(self, numels, G, *, grad_bf16=False, hp=None, seed=0, param_std=0.02, grad_std=1e-3,
+                 pad=0, launch=None, offload=False, chunk_bytes=None, sample=None, shared_grad=False,
+                 stream=None):
+        self.numels, self.G, self.pad = list(numels), G, pad
+        self.grad_bf16 = grad_bf16
+        self.hp = hp or dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+        self.seed, self.grad_std = seed, grad_std
+        self.offload, self.chunk_bytes = offload, chunk_bytes
+        self.stream = stream or torch.cuda.current_stream()
+        self.t = 0
+        gdt = torch.bfloat16 if grad_bf16 else torch.float32
+        self.P = [dev.FlatList(numels, pad=pad) for _ in range(G)]
+        self.M1 = [dev.FlatList(numels, pad=pad) for _ in range(G)]
+        self.V = [dev.FlatList(numels, pad=pad) for _ in range(G)]
+        if shared_grad:
+            g0 = dev.FlatList(numels, dtype=gdt, pad=pad)
+            self.Gd = [g0] * G
+        else:
+            self.Gd = [dev.FlatList(numels, dtype=gdt, pad=pad) for _ in range(G)]
+        if offload:
+            assert pad == 0
+            self.A = dev.FlatList(numels, pinned=True)
+            self.Mo = dev.FlatList(numels, pinned=True)
+        else:
+            self.A = dev.FlatList(numels, pad=pad)
+            self.Mo = dev.FlatList(numels, pad=pad)
+        self.P[0].fill_normal(seed=seed, stream=shapes.PARAM_STREAM, step=0, std=param_std)
+        for g in range(1, G):
+            self.P[g].flat.copy_(self.P[0].flat)
+        self.A.flat.copy_(self.P[0].flat)
+        torch.cuda.synchronize()
+
+        self.ctx = pier.pier_ctx_create(self.numels, G)
+        if launch:
+            pier.pier_ctx_set_launch(self.ctx, **launch)
+        for g in range(G):
+            pier.pier_bind_replica(self.ctx, g, self.P[g].tensors, self.M1[g].tensors, self.V[g].tensors,
+                                   self.Gd[g].tensors, grad_bf16)
+        if offload:
+            pier.pier_bind_outer(self.ctx, pier.PIER_LOC_HOST_PINNED, self.A.flat, self.Mo.flat)
+            wb = pier.pier_offload_workspace_bytes(self.ctx, chunk_bytes)
+            self.workspace = torch.empty(wb, dtype=torch.uint8, device="cuda")
+            self.s_in, self.s_out = torch.cuda.Stream(), torch.cuda.Stream()
+        else:
+            pier.pier_bind_outer(self.ctx, pier.PIER_LOC_DEVICE, self.A.tensors, self.Mo.tensors)
+
+        # oracle shadow on the sample
+        if sample is None:       # every element of every tensor (padding between tensors excluded)
+            st = self.P[0].starts
+            sample = np.concatenate([np.arange(s, s + n, dtype=np.int64) for s, n in zip(st, self.numels)]
+                                    + [np.zeros(0, np.int64)])
+        self.idx = np.asarray(sample, dtype=np.int64)
+        self.idx_d = torch.from_numpy(self.idx).cuda()
+        self.oP = [self._take(self.P[g].flat) for g in range(G)]
+        self.oM1 = [np.zeros(self.idx.size, np.float32) for _ in range(G)]
+        self.oV = [np.zeros(self.idx.size, np.float32) for _ in range(G)]
+        self.oA = self._take(self.A.flat)
+        self.oMo = np.zeros(self.idx.size, np.float32)
+
+    def _take(self, flat):
+        if flat.is_cuda:
+            x = flat[self.idx_d]
+        else:
+            x = flat[torch.from_numpy(self.idx)]
+        if x.dtype == torch.bfloat16:
+            return np.ascontiguousarray(x.view(torch.int16).cpu().numpy().view(np.uint16))
+        return np.ascontiguousarray(x.cpu().numpy())
+
+    def inner_steps(self, H, shared_stream=False):
+        """H AdamW steps on every replica.  shared_stream: every replica consumes the
+        same gradient draw (the synchronised lazy-start phase)."""
+        for _ in range(H):
+            self.t += 1
+            for g in range(self.G):
+                src = 0 if shared_stream else g
+                self.Gd[g].fill_normal(seed=self.seed, stream=src, step=self.t, std=self.grad_std,
+                                       hip_stream=self.stream)
+                gs = self._take(self.Gd[g].flat)           # synchronises; the oracle's copy of the bits
+                pier.pier_inner_adamw(self.ctx, g, step=self.t, stream=self.stream, **self.hp)
+                O.adamw(self.oP[g], self.oM1[g], self.oV[g], gs, step=self.t, **self.hp)
+
+    def outer(self, *, mu, lr, phase):
+        if self.offload:
+            self.stats = pier.pier_offload_stream(self.ctx, outer_lr=lr, mu=mu, phase=phase,
+                                                  chunk_bytes=self.chunk_bytes, workspace=self.workspace,
+                                                  compute_stream=self.stream, h2d_stream=self.s_in,
+                                                  d2h_stream=self.s_out, want_stats=True)
+        else:
+            pier.pier_outer_step(self.ctx, outer_lr=lr, mu=mu, phase=phase, stream=self.stream)
+        O.outer(self.oP, self.oA, self.oMo, mu=mu, lr=lr, phase=phase)
+
+    def device_state(self):
+        torch.cuda.synchronize()
+        d = {"A": self._take(self.A.flat), "Mo": self._take(self.Mo.flat)}
+        for g in range(self.G):
+            d["P%d" % g] = self._take(self.P[g].flat)
+            d["M1_%d" % g] = self._take(self.M1[g].flat)
+            d["V%d" % g] = self._take(self.V[g].flat)
+        return d
+
+    def oracle_state(self):
+        d = {"A": self.oA, "Mo": self.oMo}
+        for g in range(self.G):
+            d["P%d" % g], d["M1_%d" % g], d["V%d" % g] = self.oP[g], self.oM1[g], self.oV[g]
+        return d
+
+    def check(self, label=""):
+        """Asserts the parity bar on every buffer; returns a report dict."""
+        got, ref = self.device_state(), self.oracle_state()
+        rep = {"n_sampled": int(self.idx.size), "bit_exact": True, "max_abs_err": 0.0}
+        for k in ref:
+            g_, r_ = got[k], ref[k]
+            assert g_.shape == r_.shape
+            assert np.all(np.isfinite(g_)), (label, k)
+            ok = tol_ok(g_, r_)
+            assert ok.all(), "%s %s: %d of %d beyond 1e-6*max(1,|x|), worst %.3e" % (
+                label, k, (~ok).sum(), ok.size, np.abs(g_.astype(np.float64) - r_).max())
+            if k[0] in "MV":  # small-magnitude state: relative bar
+                ok = rel_ok(g_, r_)
+                assert ok.all(), "%s %s: relative bar, worst %.3e" % (
+                    label, k, (np.abs(g_.astype(np.float64) - r_) / (np.abs(r_) + 1e-30)).max())
+            rep["bit_exact"] &= bool(np.array_equal(g_.view(np.uint32), r_.view(np.uint32)))
+            rep["max_abs_err"] = max(rep["max_abs_err"], float(np.abs(g_.astype(np.float64) - r_).max()))
+        return rep

@@ -1,0 +1,261 @@
+"""GPU parity: the HIP library, called through its C ABI (ctypes binding), against the
+CPU oracle on identical seeded inputs.  Bar: |err| <= 1e-6 * max(1, |x|) per fp32
+element for every buffer (theta_g, m_g, v_g, anchor, M), plus a relative 1e-5 bar on
+the small-magnitude state.  Small cases compare every element; the full-size
+configurations compare a deterministic sample of element indices."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+WARMUP, PIER = 0, 1
+RAGGED = [1, 3, 5, 1023, 1025, 4096 + 7, 0, 70001, 16384, 16388, 2]
+
+
+def _harness():
+    import pier_harness
+    return pier_harness
+
+
+def _log(msg):
+    print("[pier-parity] " + msg, flush=True)
+
+
+# ------------------------------------------------------------------ config 1
+
+def test_config1_tiny_every_element():
+    H_ = _harness()
+    from pier_inputs import shapes
+    w = shapes.workloads()["tiny"]
+    _log("config 1: N=%d G=%d H=%d" % (w.N, w.G, w.H))
+    r = H_.Run(w.numels, w.G, seed=w.seed)
+    r.inner_steps(w.H)
+    rep = r.check("after inner")
+    lr, mu = w.fixed_outer
+    r.outer(mu=mu, lr=lr, phase=PIER)
+    rep = r.check("after outer")
+    _log("config 1: %s" % rep)
+    # every replica holds the new anchor
+    st = r.device_state()
+    for g in range(w.G):
+        assert np.array_equal(st["P%d" % g], st["A"])
+    assert np.abs(st["Mo"]).max() > 1e-5      # something actually happened
+
+
+# ------------------------------------------------------------------ ragged shapes, edge cases
+
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 8])
+@pytest.mark.parametrize("pad", [0, 1])
+def test_ragged_tensor_list_all_elements(G, pad):
+    """Odd sizes, an empty tensor, tensors that start off a 16-byte boundary (pad=1),
+    group counts with and without a specialised kernel; two rounds: lazy start then Pier."""
+    H_ = _harness()
+    _log("ragged G=%d pad=%d" % (G, pad))
+    r = H_.Run(RAGGED, G, pad=pad, seed=3, launch=dict(chunk_elems=4096))
+    r.inner_steps(3, shared_stream=True)
+    r.outer(mu=0.9, lr=0.0, phase=WARMUP)
+    r.check("warmup round")
+    st = r.device_state()
+    for g in range(G):
+        # anchor == model, replicas untouched.  The anchor is the fp32 mean of G identical
+        # values summed in order: exact for G <= 2, within a few ulp beyond (3 theta, 5 theta, ... round)
+        if G <= 2:
+            assert np.array_equal(st["P%d" % g], st["A"])
+        else:
+            assert np.all(np.abs(st["P%d" % g] - st["A"]) <= 2.0 ** -21 * np.abs(st["A"]))   # a few ulp
+    r.inner_steps(3)
+    r.outer(mu=0.99, lr=0.4, phase=PIER)
+    rep = r.check("pier round")
+    _log("ragged G=%d pad=%d: %s" % (G, pad, rep))
+
+
+@pytest.mark.parametrize("launch", [
+    dict(chunk_elems=1024, unroll=1), dict(chunk_elems=1024, unroll=4),
+    dict(chunk_elems=2048, unroll=2, nontemporal=0), dict(chunk_elems=65536, unroll=4, max_grid=3),
+    dict(chunk_elems=16384, unroll=2, max_grid=7, nontemporal=0),
+])
+def test_result_does_not_depend_on_launch_shape(launch):
+    H_ = _harness()
+    _log("launch shape %s" % launch)
+    outs = []
+    for L in (launch, None):
+        r = H_.Run(RAGGED + [300_000], 4, seed=5, launch=L)
+        r.inner_steps(2)
+        r.outer(mu=0.95, lr=0.8, phase=PIER)
+        r.inner_steps(1)
+        if L is launch:
+            r.check(str(launch))
+        outs.append(r.device_state())
+    for k in outs[0]:
+        assert np.array_equal(outs[0][k], outs[1][k]), k
+
+
+def test_bf16_gradients():
+    H_ = _harness()
+    _log("bf16 grads")
+    r = H_.Run(RAGGED + [200_000], 2, grad_bf16=True, seed=7)
+    r.inner_steps(4)
+    r.outer(mu=0.9, lr=1.1, phase=PIER)
+    rep = r.check("bf16")
+    _log("bf16: %s" % rep)
+    r2 = H_.Run(RAGGED, 2, grad_bf16=True, seed=7, pad=1)      # 2-byte aligned gradient tensors
+    r2.inner_steps(2)
+    r2.check("bf16 misaligned")
+
+
+def test_grad_scale_and_other_hyperparameters():
+    H_ = _harness()
+    _log("grad_scale / Table I betas")
+    hp = dict(lr=1.5e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.1, grad_scale=0.37)
+    r = H_.Run([50_000, 77], 1, hp=hp, seed=11)
+    r.inner_steps(5)
+    r.outer(mu=0.0, lr=1.0, phase=PIER)
+    r.check("grad_scale")
+
+
+def test_runs_are_deterministic():
+    H_ = _harness()
+    _log("determinism")
+    outs = []
+    for _ in range(2):
+        r = H_.Run(RAGGED + [500_000], 8, seed=13)
+        r.inner_steps(2)
+        r.outer(mu=0.9, lr=1.1, phase=PIER)
+        outs.append(r.device_state())
+    for k in outs[0]:
+        assert np.array_equal(outs[0][k], outs[1][k]), k
+
+
+# ------------------------------------------------------------------ host offload
+
+@pytest.mark.parametrize("chunk_bytes", [1 << 20, 1_000_016, 1 << 30, 4096])
+@pytest.mark.parametrize("phase", [WARMUP, PIER])
+def test_offload_is_bit_identical_to_resident(chunk_bytes, phase):
+    H_ = _harness()
+    numels = [300_000, 1023 * 4, 4, 0, 1_200_000, 20, 64]
+    if chunk_bytes == 4096:
+        numels = [3000, 1024, 4, 0, 5000, 20]          # many tiny pieces
+    _log("offload chunk_bytes=%d phase=%d" % (chunk_bytes, phase))
+    res = H_.Run(numels, 4, seed=17)
+    off = H_.Run(numels, 4, seed=17, offload=True, chunk_bytes=chunk_bytes)
+    for r in (res, off):
+        r.inner_steps(2, shared_stream=(phase == WARMUP))
+        r.outer(mu=0.95, lr=0.6, phase=phase)
+        r.inner_steps(1)
+        r.outer(mu=0.9, lr=1.1, phase=phase)                   # second call re-uses plan, slots, events
+    off.check("offload")
+    a, b = res.device_state(), off.device_state()
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    st = off.stats
+    assert st.n_pieces >= 1 and 1 <= st.n_slots <= 4
+    assert st.h2d_bytes == 8.0 * sum(numels) and st.d2h_bytes == st.h2d_bytes
+    assert st.wall_ms > 0 and st.kernel_ms > 0
+    _log("offload stats pieces=%d slots=%d wall=%.3f ms" % (st.n_pieces, st.n_slots, st.wall_ms))
+
+
+def test_offload_with_odd_sized_tensors():
+    """Flat host arrays pack tensors back to back, so odd sizes put later tensors off
+    the 16-byte grid: the kernel must take its scalar path there, same numbers."""
+    H_ = _harness()
+    numels = [1001, 3, 70_001, 2, 5000]
+    _log("offload odd sizes")
+    res = H_.Run(numels, 2, seed=19)
+    off = H_.Run(numels, 2, seed=19, offload=True, chunk_bytes=65536)
+    for r in (res, off):
+        r.inner_steps(2)
+        r.outer(mu=0.9, lr=0.7, phase=PIER)
+    off.check("offload odd")
+    a, b = res.device_state(), off.device_state()
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+
+
+# ------------------------------------------------------------------ error paths (host-side checks)
+
+def test_argument_errors_are_reported_not_launched():
+    import paper_2511_17849_amd as pier
+    _log("argument errors")
+    n = [1000, 24]
+    ctx = pier.pier_ctx_create(n, 2)
+    dev_t = [torch.zeros(k, device="cuda") for k in n]
+    host_t = [torch.zeros(k) for k in n]
+    with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):
+        pier.pier_inner_adamw(ctx, 0, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1)
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_bind_replica(ctx, 0, host_t, dev_t, dev_t, dev_t)            # host memory
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_bind_replica(ctx, 5, dev_t, dev_t, dev_t, dev_t)             # no such replica
+    short = [torch.zeros(10, device="cuda"), dev_t[1]]
+    big = torch.zeros(1000 + 64, device="cuda")
+    with pytest.raises(pier.PierError, match="PIER_ERR_ALIGNMENT"):
+        pier.pier_bind_replica(ctx, 0, [big.data_ptr() + 2, dev_t[1]], dev_t, dev_t, dev_t)
+    del short
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_bind_replica(ctx, 0, [None, dev_t[1]], dev_t, dev_t, dev_t)  # NULL for a non-empty tensor
+    P = [[torch.zeros(k, device="cuda") for k in n] for _ in range(4)]
+    pier.pier_bind_replica(ctx, 0, *P)
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_inner_adamw(ctx, 0, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=0)
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_inner_adamw(ctx, 0, lr=1e-3, beta1=1.0, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1)
+    with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):
+        pier.pier_outer_step(ctx, outer_lr=0.7, mu=0.9, phase=PIER)           # replica 1 unbound
+    pier.pier_bind_replica(ctx, 1, *P)
+    with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):
+        pier.pier_outer_step(ctx, outer_lr=0.7, mu=0.9, phase=PIER)           # outer state unbound
+    pier.pier_bind_outer(ctx, pier.PIER_LOC_DEVICE, dev_t, dev_t)
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_outer_step(ctx, outer_lr=0.7, mu=0.9, phase=7)
+    with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):
+        pier.pier_offload_stream(ctx, outer_lr=0.7, mu=0.9, phase=PIER, chunk_bytes=1 << 20,
+                                 workspace=torch.zeros(1 << 22, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_bind_outer(ctx, pier.PIER_LOC_HOST_PINNED, torch.zeros(1024), torch.zeros(1024))  # not pinned
+    pa, pm = torch.zeros(1024, pin_memory=True), torch.zeros(1024, pin_memory=True)
+    pier.pier_bind_outer(ctx, pier.PIER_LOC_HOST_PINNED, pa, pm)
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_offload_stream(ctx, outer_lr=0.7, mu=0.9, phase=PIER, chunk_bytes=1000,     # not /16
+                                 workspace=torch.zeros(1 << 22, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_offload_stream(ctx, outer_lr=0.7, mu=0.9, phase=PIER, chunk_bytes=1 << 20,
+                                 workspace=torch.zeros(64, dtype=torch.uint8, device="cuda"))  # too small
+    torch.cuda.synchronize()
+    # nothing above may have modified the buffers
+    for lst in P:
+        for t_ in lst:
+            assert float(t_.abs().sum()) == 0.0
+
+
+def test_all_empty_model_is_a_no_op():
+    import paper_2511_17849_amd as pier
+    ctx = pier.pier_ctx_create([0, 0], 1)
+    e = [None, None]
+    pier.pier_bind_replica(ctx, 0, e, e, e, e)
+    pier.pier_bind_outer(ctx, pier.PIER_LOC_DEVICE, e, e)
+    pier.pier_inner_adamw(ctx, 0, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1)
+    pier.pier_outer_step(ctx, outer_lr=0.7, mu=0.9, phase=PIER)
+    torch.cuda.synchronize()
+
+
+def test_device_generator_matches_host_generator():
+    """The device input generator against its numpy twin: same Philox stream, normal
+    transform equal to float rounding of log/sin/cos."""
+    from pier_inputs import device as dev, generator as gen
+    n = 100_003
+    t = torch.empty(n, device="cuda")
+    dev.fill_normal(t, seed=5, stream=3, step=9, std=1e-3)
+    host = gen.normal(n, seed=5, stream=3, step=9, std=1e-3)
+    d = t.cpu().numpy()
+    assert np.max(np.abs(d - host)) < 5e-9                     # 5e-6 of one std
+    assert abs(d.std() - 1e-3) < 2e-5
+    tb = torch.empty(n, device="cuda", dtype=torch.bfloat16)
+    dev.fill_normal(tb, seed=5, stream=3, step=9, std=1e-3)
+    hb = gen.bf16_bits_to_f32(gen.to_bf16_bits(host))
+    db = tb.float().cpu().numpy()
+    assert np.mean(db != hb) < 1e-3                            # a rounding tie may flip a handful
+    assert np.max(np.abs(db - hb)) <= 2.0 ** -8 * np.abs(hb).max()
+    part = torch.empty(1000, device="cuda")
+    dev.fill_normal(part, seed=5, stream=3, step=9, std=1e-3, first_elem=5000)
+    assert torch.equal(part, t[5000:6000])
