@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the Pier optimizer hot path on one MI355X.
+
+A "step" is one outer round of the whole path on one batch of synthetic input:
+H inner AdamW launches for each of the G group replicas (pier_inner_adamw), then
+one outer step (pier_outer_step) - at the GPT-2 XL configuration by default
+(N = 1 557 611 200 fp32 parameters, G = 8, H = 100: 800 + 1 kernel launches per
+step).  All state and one gradient buffer per replica are resident in HBM before
+the timed region; the gradients are reused by every inner step (their values do not
+change the kernels' work).  Prints ONE JSON line.
+
+`value` = parameters updated per second = N * (G*H + 1) / seconds per step, where an
+inner launch updates the N parameters of one replica and the outer step the N
+parameter positions of the synchronised model.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X published HBM3E peak
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the
+# same counters' reading of a plain copy kernel); summary in
+# profiles/kernels_gpt2_xl_hbm_traffic_pmc.md.  Only valid for the workload it was taken on.
+MEASURED_TRAFFIC_GB = {"gpt2_xl": {"adamw": 43.808, "outer": 124.824}}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="gpt2_xl")
+    ap.add_argument("--inner-steps", type=int, default=0, help="override H (inner steps per round)")
+    ap.add_argument("--no-offload", action="store_true", help="skip the host-offload measurement")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk-mib", type=int, default=256, help="offload piece size")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, budget_s=15.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: n
+    elements of the flat parameter space, G replicas, a few inner steps and one outer
+    step per round.  Single thread (the oracle is single-threaded)."""
+    import numpy as np
+    from oracle import pier_oracle as O
+    n, G, H = 1 << 22, w.G, 4
+    rng = np.random.default_rng(0)
+    P = [rng.normal(0, w.param_std, n).astype(np.float32) for _ in range(G)]
+    M = [np.zeros(n, np.float32) for _ in range(G)]
+    V = [np.zeros(n, np.float32) for _ in range(G)]
+    Gr = [rng.normal(0, w.grad_std, n).astype(np.float32) for _ in range(G)]
+    a, Mo = P[0].copy(), np.zeros(n, np.float32)
+    hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay)
+    lr_o, mu = w.fixed_outer or (1.1, 0.9)
+    O.adamw(P[0], M[0], V[0], Gr[0], step=1, **hp)          # warm the library / page in
+    t0 = time.perf_counter()
+    rounds, t = 0, 1
+    while True:
+        for _ in range(H):
+            t += 1
+            for g in range(G):
+                O.adamw(P[g], M[g], V[g], Gr[g], step=t, **hp)
+        O.outer(P, a, Mo, mu=mu, lr=lr_o, phase=O.PIER)
+        rounds += 1
+        dt = time.perf_counter() - t0
+        if dt > budget_s:
+            break
+    return {"value": rounds * n * (G * H + 1) / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
+            "sample": "%d rounds of (G=%d x H=%d AdamW steps + 1 outer step) on a %d-element slice, "
+                      "single-threaded C oracle, %.1f s" % (rounds, G, H, n, dt)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not "
+              "supported, run with --gpus 1" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2511_17849_amd as pier
+    from pier_inputs import shapes, device as dev
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    w = shapes.workloads()[args.workload]
+    N, G = w.N, w.G
+    H = args.inner_steps or w.H
+    K, W = args.steps, args.warmup
+    bf16 = w.grad_bf16
+    hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay)
+    lr_o, mu = w.fixed_outer or (1.1, 0.9)
+    stream = torch.cuda.Stream()
+
+    # HBM layout: buffers of one kind are allocated together (all theta_g, then all m_g,
+    # all v_g, all gradients, then anchor and M), so the four streams one AdamW launch
+    # touches lie tens of GiB apart
+    gdt = torch.bfloat16 if bf16 else torch.float32
+    P = [dev.FlatList(w.numels, zero=False) for _ in range(G)]
+    M1 = [dev.FlatList(w.numels) for _ in range(G)]
+    V = [dev.FlatList(w.numels) for _ in range(G)]
+    Gd = [dev.FlatList(w.numels, dtype=gdt, zero=False) for _ in range(G)]
+    A, Mo = dev.FlatList(w.numels, zero=False), dev.FlatList(w.numels)
+    with torch.cuda.stream(stream):
+        dev.init_params(P[0], w)
+        for g in range(1, G):
+            P[g].flat.copy_(P[0].flat)
+        A.flat.copy_(P[0].flat)
+        for g in range(G):
+            Gd[g].fill_normal(seed=w.seed, stream=g, step=1, std=w.grad_std, hip_stream=stream)
+    stream.synchronize()
+
+    ctx = pier.pier_ctx_create(w.numels, G)
+    for g in range(G):
+        pier.pier_bind_replica(ctx, g, P[g].tensors, M1[g].tensors, V[g].tensors, Gd[g].tensors, bf16)
+    pier.pier_bind_outer(ctx, pier.PIER_LOC_DEVICE, A.tensors, Mo.tensors)
+
+    t_step = [0]
+
+    def one_round(ev=None):
+        if ev:
+            ev[0].record(stream)
+        for _ in range(H):
+            t_step[0] += 1
+            for g in range(G):
+                pier.pier_inner_adamw(ctx, g, step=t_step[0], stream=stream, **hp)
+        if ev:
+            ev[1].record(stream)
+        pier.pier_outer_step(ctx, outer_lr=lr_o, mu=mu, phase=pier.PIER_PHASE_PIER, stream=stream)
+        if ev:
+            ev[2].record(stream)
+
+    for _ in range(W):
+        one_round()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        one_round(evs[k])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    inner_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / (K * G * H)     # per AdamW launch
+    outer_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / K               # per outer launch
+    gbytes = 26 if bf16 else 28
+    inner_gbps = gbytes * N / inner_ms / 1e6
+    outer_bpe = 8 * G + 16
+    outer_gbps = outer_bpe * N / outer_ms / 1e6
+    traffic = MEASURED_TRAFFIC_GB.get(w.name, {})
+    ms_per_step = dt / K * 1e3
+    value = N * (G * H + 1) / (dt / K)
+
+    out = {
+        "metric": "params updated/sec, inner AdamW (G x H launches) + outer Pier step, 1 GPU",
+        "value": value, "unit": "params/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if not bf16 else "f32 (bf16 gradients)", "data": "synthetic",
+        "config": {"workload": "%s: N=%d fp32 params in %d tensors, G=%d replicas, H=%d inner steps per "
+                               "round, resident outer step (mu=%.2f, outer lr=%.2f)" %
+                               (w.name, N, len(w.numels), G, H, mu, lr_o)},
+        "roofline": {"bound": "hbm", "kernel": "adamw_kernel (pier_inner_adamw)", "achieved": inner_gbps,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": inner_gbps / HBM_PEAK_GBPS,
+                     "traffic": traffic.get("adamw"), "traffic_unit": "GB per launch (rocprofv3 pmc)",
+                     "algorithmic_GB_per_launch": gbytes * N / 1e9,
+                     "bytes_per_param": gbytes, "avg_launch_ms": inner_ms,
+                     "launches_timed": K * G * H},
+        "roofline_outer": {"bound": "hbm", "kernel": "outer_kernel (pier_outer_step, Pier phase)",
+                           "achieved": outer_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                           "frac": outer_gbps / HBM_PEAK_GBPS, "traffic": traffic.get("outer"),
+                           "traffic_unit": "GB per launch (rocprofv3 pmc)",
+                           "algorithmic_GB_per_launch": outer_bpe * N / 1e9,
+                           "bytes_per_param": outer_bpe, "avg_launch_ms": outer_ms, "launches_timed": K},
+    }
+
+    if not args.no_offload:
+        # the same outer step with anchor and M streamed from pinned host memory
+        chunk = args.chunk_mib << 20
+        hA = torch.empty(N, dtype=torch.float32, pin_memory=True)
+        hM = torch.zeros(N, dtype=torch.float32, pin_memory=True)
+        hA.copy_(A.flat)
+        pier.pier_bind_outer(ctx, pier.PIER_LOC_HOST_PINNED, hA, hM)
+        ws = torch.empty(pier.pier_offload_workspace_bytes(ctx, chunk), dtype=torch.uint8, device="cuda")
+        s_in, s_out = torch.cuda.Stream(), torch.cuda.Stream()
+        best = None
+        for _ in range(3):
+            st = pier.pier_offload_stream(ctx, outer_lr=lr_o, mu=mu, phase=pier.PIER_PHASE_PIER,
+                                          chunk_bytes=chunk, workspace=ws, compute_stream=stream,
+                                          h2d_stream=s_in, d2h_stream=s_out, want_stats=True)
+            if best is None or st.wall_ms < best.wall_ms:
+                best = st
+        out["offload"] = {
+            "entry": "pier_offload_stream", "chunk_mib": args.chunk_mib, "pieces": best.n_pieces,
+            "slots": best.n_slots, "wall_ms": best.wall_ms,
+            "h2d_GBps": best.h2d_bytes / best.h2d_ms / 1e6, "d2h_GBps": best.d2h_bytes / best.d2h_ms / 1e6,
+            "pcie_GBps_each_way_over_wall": best.h2d_bytes / best.wall_ms / 1e6,
+            "kernel_ms": best.kernel_ms,
+            "overlap": max(best.h2d_ms, best.d2h_ms, best.kernel_ms) / best.wall_ms,
+            "params_per_s": N / best.wall_ms * 1e3,
+        }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
