@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--inner-steps", type=int, default=0, help="override H (inner steps per round)")
     ap.add_argument("--no-offload", action="store_true", help="skip the host-offload measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-arena", action="store_true", help="plain allocations instead of the probed arena")
     ap.add_argument("--chunk-mib", type=int, default=256, help="offload piece size")
     return ap.parse_args()
 
@@ -99,15 +100,20 @@ def main():
     lr_o, mu = w.fixed_outer or (1.1, 0.9)
     stream = torch.cuda.Stream()
 
-    # HBM layout: buffers of one kind are allocated together (all theta_g, then all m_g,
-    # all v_g, all gradients, then anchor and M), so the four streams one AdamW launch
-    # touches lie tens of GiB apart
+    # HBM layout: one arena over (almost) all free HBM is probed for its address classes and
+    # the buffers one launch streams together are carved from different classes; if the
+    # arena cannot be had, buffers are allocated kind by kind instead
     gdt = torch.bfloat16 if bf16 else torch.float32
-    P = [dev.FlatList(w.numels, zero=False) for _ in range(G)]
-    M1 = [dev.FlatList(w.numels) for _ in range(G)]
-    V = [dev.FlatList(w.numels) for _ in range(G)]
-    Gd = [dev.FlatList(w.numels, dtype=gdt, zero=False) for _ in range(G)]
-    A, Mo = dev.FlatList(w.numels, zero=False), dev.FlatList(w.numels)
+    arena, placement = None, "separate allocations, kind by kind"
+    if not args.no_arena:
+        try:
+            free, _ = torch.cuda.mem_get_info()
+            arena = pier.HbmArena(free - (8 << 30), stream=stream)
+            placement = "probed arena of %d GiB, %d address classes" % (arena.buf.numel() >> 30, arena.n_classes)
+        except (MemoryError, RuntimeError, pier.PierError) as e:
+            print("bench.py: no arena (%s); allocating kind by kind" % e, file=sys.stderr)
+    S = dev.PlacedState(w.numels, G, grad_dtype=gdt, arena=arena)
+    P, M1, V, Gd, A, Mo = S.P, S.M1, S.V, S.Gd, S.A, S.Mo
     with torch.cuda.stream(stream):
         dev.init_params(P[0], w)
         for g in range(1, G):
@@ -164,7 +170,8 @@ def main():
         "dtype": "f32" if not bf16 else "f32 (bf16 gradients)", "data": "synthetic",
         "config": {"workload": "%s: N=%d fp32 params in %d tensors, G=%d replicas, H=%d inner steps per "
                                "round, resident outer step (mu=%.2f, outer lr=%.2f)" %
-                               (w.name, N, len(w.numels), G, H, mu, lr_o)},
+                               (w.name, N, len(w.numels), G, H, mu, lr_o),
+                   "hbm_placement": placement},
         "roofline": {"bound": "hbm", "kernel": "adamw_kernel (pier_inner_adamw)", "achieved": inner_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": inner_gbps / HBM_PEAK_GBPS,
                      "traffic": traffic.get("adamw"), "traffic_unit": "GB per launch (rocprofv3 pmc)",

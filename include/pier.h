@@ -81,8 +81,9 @@ pier_status pier_ctx_set_launch(pier_ctx* ctx, int64_t chunk_elems, int unroll, 
 /* Binds replica `replica` (0-based).  p, m, v, grad are HOST arrays of n_tensors
  * DEVICE pointers: parameters theta_g, AdamW first and second moments (fp32), and
  * the gradient of each tensor, fp32 or (grad_is_bf16 != 0) bfloat16.  A tensor with
- * numel 0 may have NULL pointers.  May be called again to re-point a replica
- * (synchronous small copy). */
+ * numel 0 may have NULL pointers.  May be called again to re-point a replica: the
+ * tables are rewritten with a synchronous small copy, so no launch of this context
+ * may be in flight during a re-bind (the same holds for pier_bind_outer). */
 pier_status pier_bind_replica(pier_ctx* ctx, int replica, float* const* p, float* const* m,
                               float* const* v, const void* const* grad, int grad_is_bf16);
 
@@ -156,6 +157,22 @@ pier_status pier_offload_workspace_bytes(const pier_ctx* ctx, size_t chunk_bytes
 pier_status pier_offload_stream(pier_ctx* ctx, const pier_outer_hp* hp, size_t chunk_bytes,
                                 void* workspace, size_t workspace_bytes, void* compute_stream,
                                 void* h2d_stream, void* d2h_stream, pier_offload_stats* stats);
+
+/* --------------------------------------------------------- placement probe
+ * Not an operation of the paper: a measurement aid for laying the caller's buffers out
+ * in MI355X's HBM.  The two kernels stream several buffers in place at once, and the
+ * rate they sustain depends on where those buffers sit relative to each other: the
+ * 288 GiB behave as three classes of 96 GiB (buffers streamed together from different
+ * classes reach ~6.5 TB/s, from one class ~6.0 TB/s).  This call classifies the
+ * n_granules consecutive granules of granule_bytes (multiple of 2 MiB, >= 512 MiB)
+ * that start at the device pointer `arena`, by timing a two-buffer in-place streaming
+ * pass between granules: class_out[g] (host array) receives a small class id, equal for
+ * granules that behave as one class.  A caller then places buffers that one launch
+ * touches together (theta_g, m_g, v_g; the theta of different replicas, anchor, M) in
+ * different classes.  Synchronous (a second or two); OVERWRITES the arena's contents;
+ * enqueues on hip_stream and waits for it. */
+pier_status pier_hbm_probe(void* arena, size_t bytes, size_t granule_bytes, int32_t* class_out,
+                           int n_granules, void* hip_stream);
 
 /* ------------------------------------------------------------- schedules
  * Pure host helpers; t = iteration (1-based), T = total iterations (> 0). */

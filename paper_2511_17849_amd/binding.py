@@ -69,6 +69,7 @@ def _load():
         "pier_offload_workspace_bytes": (i32, [vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]),
         "pier_offload_stream": (i32, [vp, ctypes.POINTER(OuterHP), ctypes.c_size_t, vp, ctypes.c_size_t,
                                       vp, vp, vp, ctypes.POINTER(OffloadStats)]),
+        "pier_hbm_probe": (i32, [vp, ctypes.c_size_t, ctypes.c_size_t, ctypes.POINTER(ctypes.c_int32), i32, vp]),
         "pier_mu_schedule": (f32, [i64, i64]),
         "pier_outer_lr_schedule": (f32, [i64, i64]),
         "pier_outer_schedule": (i32, [i64, i64, ctypes.POINTER(OuterHP)]),
@@ -196,6 +197,15 @@ def pier_offload_stream(ctx, *, outer_lr, mu, phase, chunk_bytes, workspace, com
                                        int(wbytes), _stream(compute_stream), _stream(h2d_stream),
                                        _stream(d2h_stream), ctypes.byref(stats) if want_stats else None))
     return stats
+
+
+def pier_hbm_probe(arena, granule_bytes, stream=None):
+    """Class id of every granule of the device tensor ``arena`` (its contents are overwritten)."""
+    nbytes = arena.numel() * arena.element_size()
+    n = int(nbytes // granule_bytes)
+    out = (ctypes.c_int32 * max(n, 1))()
+    _check(_load().pier_hbm_probe(arena.data_ptr() or None, nbytes, int(granule_bytes), out, n, _stream(stream)))
+    return list(out[:n])
 
 
 def pier_mu_schedule(t, T):

@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <new>
@@ -74,8 +75,8 @@ struct pier_ctx {
     std::vector<char> rep_bound;
     std::vector<char> rep_bf16;
 
-    std::vector<OuterPtrs> h_outer;
-    OuterPtrs* d_outer = nullptr;
+    std::vector<uint64_t> h_rows;  // n_tensors rows of outer_row_words(n_replicas) words
+    uint64_t* d_rows = nullptr;
     bool outer_bound = false;
     pier_loc outer_loc = PIER_LOC_DEVICE;
     float* host_a = nullptr;
@@ -130,8 +131,8 @@ pier_status ensure_device(pier_ctx* c)
     const size_t nrep = static_cast<size_t>(c->n_replicas) * c->n_tensors;
     PIER_HIP(hipMalloc(reinterpret_cast<void**>(&c->d_rep), sizeof(RepPtrs) * nrep));
     PIER_HIP(hipMemset(c->d_rep, 0, sizeof(RepPtrs) * nrep));
-    PIER_HIP(hipMalloc(reinterpret_cast<void**>(&c->d_outer), sizeof(OuterPtrs) * c->n_tensors));
-    PIER_HIP(hipMemcpy(c->d_outer, c->h_outer.data(), sizeof(OuterPtrs) * c->n_tensors,
+    PIER_HIP(hipMalloc(reinterpret_cast<void**>(&c->d_rows), sizeof(uint64_t) * c->h_rows.size()));
+    PIER_HIP(hipMemcpy(c->d_rows, c->h_rows.data(), sizeof(uint64_t) * c->h_rows.size(),
                        hipMemcpyHostToDevice));
     PIER_HIP(hipEventCreate(&c->offload_done));
     c->device = dev;
@@ -251,8 +252,9 @@ pier_status pier_ctx_create(pier_ctx** out, int n_tensors, const int64_t* numel,
         c->h_rep.assign(static_cast<size_t>(n_replicas) * n_tensors, RepPtrs{});
         c->rep_bound.assign(n_replicas, 0);
         c->rep_bf16.assign(n_replicas, 0);
-        c->h_outer.assign(n_tensors, OuterPtrs{});
-        for (int i = 0; i < n_tensors; ++i) c->h_outer[i].flat_start = c->flat_start[i];
+        const size_t rw = outer_row_words(n_replicas);
+        c->h_rows.assign(rw * n_tensors, 0);
+        for (int i = 0; i < n_tensors; ++i) c->h_rows[rw * i + 2] = static_cast<uint64_t>(c->flat_start[i]);
     } catch (const std::bad_alloc&) {
         delete c;
         return fail(PIER_ERR_OOM, "out of host memory");
@@ -267,7 +269,7 @@ pier_status pier_ctx_destroy(pier_ctx* c)
     if (c->device >= 0) {
         if (c->d_chunks) (void)hipFree(c->d_chunks);
         if (c->d_rep) (void)hipFree(c->d_rep);
-        if (c->d_outer) (void)hipFree(c->d_outer);
+        if (c->d_rows) (void)hipFree(c->d_rows);
         for (auto& kv : c->plans) free_plan(kv.second);
         if (c->offload_done) (void)hipEventDestroy(c->offload_done);
     }
@@ -283,8 +285,8 @@ pier_status pier_ctx_set_launch(pier_ctx* c, int64_t chunk_elems, int unroll, in
     if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
     if (c->device >= 0) return fail(PIER_ERR_STATE, "launch shape must be set before the first bind");
     if (chunk_elems != 0) {
-        if (chunk_elems < 1024 || chunk_elems % 1024 || chunk_elems > (1 << 30))
-            return fail(PIER_ERR_INVALID_ARG, "chunk_elems = %lld: need a multiple of 1024 in [1024, 2^30]",
+        if (chunk_elems < 1024 || chunk_elems % 1024 || chunk_elems > (1 << 26))
+            return fail(PIER_ERR_INVALID_ARG, "chunk_elems = %lld: need a multiple of 1024 in [1024, 2^26]",
                         static_cast<long long>(chunk_elems));
     }
     if (unroll != 0 && unroll != 1 && unroll != 2 && unroll != 4)
@@ -320,6 +322,11 @@ pier_status pier_bind_replica(pier_ctx* c, int replica, float* const* p, float* 
     for (int i = 0; i < c->n_tensors; ++i) row[i] = RepPtrs{p[i], m[i], v[i], grad[i]};
     PIER_HIP(hipMemcpy(c->d_rep + static_cast<size_t>(replica) * c->n_tensors, row,
                        sizeof(RepPtrs) * c->n_tensors, hipMemcpyHostToDevice));
+    const size_t rw = outer_row_words(c->n_replicas);
+    for (int i = 0; i < c->n_tensors; ++i)
+        c->h_rows[rw * i + kOuterRowHead + replica] = reinterpret_cast<uint64_t>(p[i]);
+    PIER_HIP(hipMemcpy(c->d_rows, c->h_rows.data(), sizeof(uint64_t) * c->h_rows.size(),
+                       hipMemcpyHostToDevice));
     c->rep_bound[replica] = 1;
     c->rep_bf16[replica] = grad_is_bf16 ? 1 : 0;
     return PIER_OK;
@@ -339,11 +346,12 @@ pier_status pier_bind_outer(pier_ctx* c, pier_loc loc, float* const* anchor,
             if ((st = check_device_range(anchor[i], c->numel[i], 4, c->device, "anchor", i)) != PIER_OK) return st;
             if ((st = check_device_range(momentum[i], c->numel[i], 4, c->device, "momentum", i)) != PIER_OK) return st;
         }
+        const size_t rw = outer_row_words(c->n_replicas);
         for (int i = 0; i < c->n_tensors; ++i) {
-            c->h_outer[i].a = anchor[i];
-            c->h_outer[i].M = momentum[i];
+            c->h_rows[rw * i + 0] = reinterpret_cast<uint64_t>(anchor[i]);
+            c->h_rows[rw * i + 1] = reinterpret_cast<uint64_t>(momentum[i]);
         }
-        PIER_HIP(hipMemcpy(c->d_outer, c->h_outer.data(), sizeof(OuterPtrs) * c->n_tensors,
+        PIER_HIP(hipMemcpy(c->d_rows, c->h_rows.data(), sizeof(uint64_t) * c->h_rows.size(),
                            hipMemcpyHostToDevice));
         c->host_a = c->host_M = nullptr;
     } else {
@@ -412,9 +420,9 @@ pier_status pier_outer_step(pier_ctx* c, const pier_outer_hp* hp, void* hip_stre
     if (!c->outer_bound || c->outer_loc != PIER_LOC_DEVICE)
         return fail(PIER_ERR_STATE, "anchor and momentum are not bound as device tensors");
     if ((st = ensure_device(c)) != PIER_OK) return st;
-    PIER_HIP(launch_outer(c->d_chunks, c->n_chunks, c->d_rep, c->n_tensors, c->n_replicas, c->d_outer,
-                          nullptr, nullptr, 0, hp->mu, hp->outer_lr, hp->phase == PIER_PHASE_PIER,
-                          c->shape, static_cast<hipStream_t>(hip_stream)));
+    PIER_HIP(launch_outer(c->d_chunks, c->n_chunks, c->d_rows, c->n_replicas, nullptr, nullptr, 0,
+                          hp->mu, hp->outer_lr, hp->phase == PIER_PHASE_PIER, c->shape,
+                          static_cast<hipStream_t>(hip_stream)));
     return PIER_OK;
 }
 
@@ -518,9 +526,9 @@ pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chu
         PIER_HIP(hipStreamWaitEvent(sc, EV(k, H2D_E), 0));
         PIER_HIP(hipEventRecord(EV(k, KER_B), sc));
         PIER_HIP(launch_outer(plan.d_chunks + plan.chunk_begin[k],
-                              plan.chunk_begin[k + 1] - plan.chunk_begin[k], c->d_rep, c->n_tensors,
-                              c->n_replicas, c->d_outer, sa, sM, lo, hp->mu, hp->outer_lr,
-                              hp->phase == PIER_PHASE_PIER, c->shape, sc));
+                              plan.chunk_begin[k + 1] - plan.chunk_begin[k], c->d_rows, c->n_replicas,
+                              sa, sM, lo, hp->mu, hp->outer_lr, hp->phase == PIER_PHASE_PIER,
+                              c->shape, sc));
         PIER_HIP(hipEventRecord(EV(k, KER_E), sc));
 
         // stage 3: offload the new model and momentum of this piece
@@ -552,6 +560,90 @@ pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chu
         PIER_HIP(hipEventElapsedTime(&wall, EV(0, H2D_B), EV(n_pieces - 1, D2H_E)));
         stats->wall_ms = wall;
     }
+    return PIER_OK;
+}
+
+pier_status pier_hbm_probe(void* arena, size_t bytes, size_t granule_bytes, int32_t* class_out,
+                           int n_granules, void* hip_stream)
+{
+    if (!arena || !class_out) return fail(PIER_ERR_INVALID_ARG, "arena or class_out is NULL");
+    const size_t kMiB = 1u << 20;
+    if (granule_bytes < 512 * kMiB || granule_bytes % (2 * kMiB))
+        return fail(PIER_ERR_INVALID_ARG, "granule_bytes must be a multiple of 2 MiB, at least 512 MiB");
+    if (reinterpret_cast<uintptr_t>(arena) % 16) return fail(PIER_ERR_ALIGNMENT, "arena is not aligned to 16 bytes");
+    if (n_granules < 2 || n_granules > 4096 || static_cast<size_t>(n_granules) > bytes / granule_bytes)
+        return fail(PIER_ERR_INVALID_ARG, "n_granules = %d does not fit %zu bytes of %zu-byte granules (need 2..4096)",
+                    n_granules, bytes, granule_bytes);
+    int dev = -1;
+    PIER_HIP(hipGetDevice(&dev));
+    pier_status st = check_device_range(arena, static_cast<int64_t>(granule_bytes) * n_granules, 1, dev, "arena", 0);
+    if (st != PIER_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    PIER_HIP(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return fail(PIER_ERR_HIP, "hipEventCreate failed");
+    }
+    // probe up to 2 GiB of each granule: far more than the 256 MB memory-side cache, and
+    // long enough (> 1 ms per pass) that ramp-up and tail do not blur the two rate levels
+    const size_t probe_bytes = std::min<size_t>(granule_bytes, 2048 * kMiB);
+    const int64_t n4 = static_cast<int64_t>(probe_bytes / 16);
+    char* base = static_cast<char*>(arena);
+    auto granule = [&](int g) { return reinterpret_cast<float*>(base + static_cast<size_t>(g) * granule_bytes); };
+    hipError_t err = hipSuccess;
+    const bool verbose = std::getenv("PIER_PROBE_VERBOSE") != nullptr;
+    // streaming rate (TB/s) of one in-place pass over granules a and b, faster of two
+    auto measure = [&](int a, int b) -> double {
+        double bestr = 0.0;
+        if (err == hipSuccess) err = launch_probe(granule(a), granule(b), n4, s);   // warm
+        for (int r = 0; r < 2 && err == hipSuccess; ++r) {
+            err = hipEventRecord(e0, s);
+            if (err == hipSuccess) err = launch_probe(granule(a), granule(b), n4, s);
+            if (err == hipSuccess) err = hipEventRecord(e1, s);
+            if (err == hipSuccess) err = hipEventSynchronize(e1);
+            float ms = 0.f;
+            if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
+            if (err == hipSuccess && ms > 0.f) bestr = std::max(bestr, 4.0 * probe_bytes / (ms * 1e9));
+        }
+        if (verbose) fprintf(stderr, "[pier probe] %d x %d: %.3f TB/s\n", a, b, bestr);
+        return bestr;
+    };
+    // Two granules of one class stream at 5.5-6.3 TB/s together (it varies with their
+    // distance), two of different classes at 6.4-6.6 TB/s.  The level of the fast group is
+    // taken from a first sweep against granule 0; an arena whose sweep never reaches
+    // 6.3 TB/s lies in one class.
+    double fast = 0.0;
+    const int stride = std::max(1, n_granules / 24);
+    for (int t = 1; t < n_granules; t += stride) fast = std::max(fast, measure(0, t));
+    const bool one_class = fast < 6.3;
+    const double thr = 0.967 * fast;
+    std::vector<std::vector<int>> classes;
+    for (int t = 0; t < n_granules && err == hipSuccess; ++t) {
+        int pick = -1;
+        double lowest = 1e30;
+        if (one_class) {
+            pick = classes.empty() ? -1 : 0;
+            lowest = 0.0;
+        } else {
+            for (size_t c = 0; c < classes.size() && err == hipSuccess; ++c) {
+                // against the first and the latest member of the class; the slower pairing
+                // decides (a few same-class distances stream almost as fast as cross-class pairs)
+                const std::vector<int>& m = classes[c];
+                double r = measure(m.front(), t);
+                if (m.back() != m.front() && r >= thr) r = std::min(r, measure(m.back(), t));
+                if (r < lowest) { lowest = r; pick = static_cast<int>(c); }
+            }
+        }
+        if (pick >= 0 && (lowest < thr || classes.size() >= 8)) classes[pick].push_back(t);
+        else classes.push_back(std::vector<int>(1, t));
+    }
+    if (err == hipSuccess)
+        for (size_t c = 0; c < classes.size(); ++c)
+            for (int t : classes[c]) class_out[t] = static_cast<int32_t>(c);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (err != hipSuccess) return fail(PIER_ERR_HIP, "placement probe: %s", hipGetErrorString(err));
     return PIER_OK;
 }
 

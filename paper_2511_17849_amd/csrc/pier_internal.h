@@ -24,14 +24,14 @@ struct RepPtrs {
     const void* g;
 };
 
-// Per-tensor outer state.  flat_start = number of elements in the tensors before
-// this one (its position in the flat host arrays of the offload path).
-struct OuterPtrs {
-    float* a;
-    float* M;
-    int64_t flat_start;
-    int64_t reserved;
-};
+// Per-tensor row of the outer step's table: 4 + G eight-byte words, contiguous so that
+// a workgroup fetches everything it needs about its tensor with one scalar load:
+//   word 0: anchor pointer   word 1: momentum pointer
+//   word 2: flat_start = number of elements in the tensors before this one (its
+//           position in the flat host arrays of the offload path)
+//   word 3: reserved         words 4 .. 4+G-1: theta pointers of replicas 0 .. G-1
+constexpr int kOuterRowHead = 4;
+inline size_t outer_row_words(int G) { return static_cast<size_t>(kOuterRowHead + G); }
 
 struct AdamwScalars {
     float lr, beta1, beta2, om1, om2, eps, wd, bc1, bc2, grad_scale;
@@ -48,13 +48,16 @@ constexpr int kBlock = 256;  // four 64-wide wavefronts
 hipError_t launch_adamw(const Chunk* chunks, int n_chunks, const RepPtrs* tab, bool grad_bf16,
                         const AdamwScalars& s, const LaunchShape& shape, hipStream_t stream);
 
-// rep_tab holds G * n_tensors entries, replica-major.  When flat_a != nullptr the
-// anchor and momentum of element e of the flat index space are flat_a[e - flat_lo]
-// and flat_M[e - flat_lo] (staging slot of an offload piece) and otab supplies only
-// flat_start; otherwise they are otab[tensor].a / .M.
-hipError_t launch_outer(const Chunk* chunks, int n_chunks, const RepPtrs* rep_tab, int n_tensors,
-                        int G, const OuterPtrs* otab, float* flat_a, float* flat_M,
-                        int64_t flat_lo, float mu, float lr, bool pier_phase,
-                        const LaunchShape& shape, hipStream_t stream);
+// rows: n_tensors rows of outer_row_words(G) words.  When flat_a != nullptr the anchor
+// and momentum of element e of the flat index space are flat_a[e - flat_lo] and
+// flat_M[e - flat_lo] (staging slot of an offload piece) and the rows supply only
+// flat_start and the theta pointers; otherwise words 0 and 1 are used.
+hipError_t launch_outer(const Chunk* chunks, int n_chunks, const uint64_t* rows, int G,
+                        float* flat_a, float* flat_M, int64_t flat_lo, float mu, float lr,
+                        bool pier_phase, const LaunchShape& shape, hipStream_t stream);
+
+// Two-stream in-place streaming pass used by the placement probe: reads n4 16-byte
+// vectors from x and y, writes them back to where they came from.
+hipError_t launch_probe(float* x, float* y, int64_t n4, hipStream_t stream);
 
 }  // namespace pier

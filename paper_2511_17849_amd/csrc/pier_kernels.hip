@@ -46,6 +46,21 @@ __device__ __forceinline__ void st(T* p, T x)
     else *q = x;
 }
 
+// Vector access at base + byte_off with a wave-uniform base and a 32-bit per-lane byte
+// offset: this shape lets the compiler keep the base in SGPRs and one offset VGPR for all
+// streams (global_load_dwordx4 v, v_off, s[base]) instead of a 64-bit VGPR address per stream.
+template <bool NT, typename T>
+__device__ __forceinline__ T ldo(const void* base, unsigned byte_off)
+{
+    return ld<NT>(reinterpret_cast<const T*>(static_cast<const char*>(base) + byte_off));
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ void sto(void* base, unsigned byte_off, T x)
+{
+    st<NT>(reinterpret_cast<T*>(static_cast<char*>(base) + byte_off), x);
+}
+
 __device__ __forceinline__ float bf16_to_f32(unsigned short h)
 {
     return __uint_as_float(static_cast<unsigned int>(h) << 16);
@@ -152,10 +167,7 @@ __global__ __launch_bounds__(kBlock) void adamw_kernel(const Chunk* __restrict__
                                reinterpret_cast<uintptr_t>(v)) & 15u;
         const uintptr_t gmis = reinterpret_cast<uintptr_t>(g) & (sizeof(gvec) - 1);
         if ((mis | gmis) == 0) {
-            vfloat4* p4 = reinterpret_cast<vfloat4*>(p);
-            vfloat4* m4 = reinterpret_cast<vfloat4*>(m);
-            vfloat4* v4 = reinterpret_cast<vfloat4*>(v);
-            const gvec* g4 = reinterpret_cast<const gvec*>(g);
+            constexpr unsigned kG = sizeof(gvec);
             const int n4 = len >> 2;
             int base = 0;
             for (; base + kTile <= n4; base += kTile) {
@@ -163,29 +175,31 @@ __global__ __launch_bounds__(kBlock) void adamw_kernel(const Chunk* __restrict__
                 gvec Gr[UNROLL];
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
-                    const int i = base + u * kBlock + tid;
-                    P[u] = ld<NT>(p4 + i);
-                    M[u] = ld<NT>(m4 + i);
-                    V[u] = ld<NT>(v4 + i);
-                    Gr[u] = ld<NT>(g4 + i);
+                    const unsigned i = static_cast<unsigned>(base + u * kBlock + tid);
+                    P[u] = ldo<NT, vfloat4>(p, i * 16u);
+                    M[u] = ldo<NT, vfloat4>(m, i * 16u);
+                    V[u] = ldo<NT, vfloat4>(v, i * 16u);
+                    Gr[u] = ldo<NT, gvec>(g, i * kG);
                 }
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
-                    const int i = base + u * kBlock + tid;
+                    const unsigned i = static_cast<unsigned>(base + u * kBlock + tid);
                     adamw_vec(P[u], M[u], V[u], GradVec<BF16>::widen(Gr[u]), s);
-                    st<NT>(p4 + i, P[u]);
-                    st<NT>(m4 + i, M[u]);
-                    st<NT>(v4 + i, V[u]);
+                    sto<NT>(p, i * 16u, P[u]);
+                    sto<NT>(m, i * 16u, M[u]);
+                    sto<NT>(v, i * 16u, V[u]);
                 }
             }
             // ragged last tile of the chunk
-            for (int i = base + tid; i < n4; i += kBlock) {
-                vfloat4 P = ld<NT>(p4 + i), M = ld<NT>(m4 + i), V = ld<NT>(v4 + i);
-                const gvec Gr = ld<NT>(g4 + i);
+            for (int j = base + tid; j < n4; j += kBlock) {
+                const unsigned i = static_cast<unsigned>(j);
+                vfloat4 P = ldo<NT, vfloat4>(p, i * 16u), M = ldo<NT, vfloat4>(m, i * 16u),
+                        V = ldo<NT, vfloat4>(v, i * 16u);
+                const gvec Gr = ldo<NT, gvec>(g, i * kG);
                 adamw_vec(P, M, V, GradVec<BF16>::widen(Gr), s);
-                st<NT>(p4 + i, P);
-                st<NT>(m4 + i, M);
-                st<NT>(v4 + i, V);
+                sto<NT>(p, i * 16u, P);
+                sto<NT>(m, i * 16u, M);
+                sto<NT>(v, i * 16u, V);
             }
             // up to three elements past the last whole vector
             const int i = (n4 << 2) + tid;
@@ -304,86 +318,93 @@ __device__ __forceinline__ void outer_scalar(float* const (&th)[G], float* a, fl
 }
 
 struct OuterArgs {
-    const Chunk* chunks;
-    const RepPtrs* rep_tab;
-    const OuterPtrs* otab;
     float* flat_a;
     float* flat_M;
     int64_t flat_lo;
     int n_chunks;
-    int n_tensors;
     int G;
     float mu, lr, invG;
 };
 
+// One row of the outer table as the kernel for G replicas sees it.
+template <int G>
+struct OuterRow {
+    float* a;
+    float* M;
+    int64_t flat_start;
+    int64_t reserved;
+    float* th[G];
+};
+
+// The tables are separate const __restrict__ parameters: only then may the compiler
+// read them through the scalar unit (they are never written by a kernel).
 template <int G, int UNROLL, bool FLAT, bool PIER, bool NT>
-__global__ __launch_bounds__(kBlock) void outer_kernel(OuterArgs A)
+__global__ __launch_bounds__(kBlock) void outer_kernel(const Chunk* __restrict__ chunks,
+                                                       const OuterRow<G>* __restrict__ rows,
+                                                       OuterArgs A)
 {
+    static_assert(sizeof(OuterRow<G>) == (kOuterRowHead + G) * 8, "row layout");
     const int tid = threadIdx.x;
     constexpr int kTile = kBlock * UNROLL;
 
     for (int c = blockIdx.x; c < A.n_chunks; c += gridDim.x) {
-        const Chunk ch = A.chunks[c];
-        const OuterPtrs ot = A.otab[ch.tensor];
+        const Chunk ch = chunks[c];
+        const OuterRow<G> row = rows[ch.tensor];
         float* __restrict__ a;
         float* __restrict__ M;
         if constexpr (FLAT) {
-            const int64_t e = ot.flat_start + ch.off - A.flat_lo;
+            const int64_t e = row.flat_start + ch.off - A.flat_lo;
             a = A.flat_a + e;
             M = A.flat_M + e;
         } else {
-            a = ot.a + ch.off;
-            M = ot.M + ch.off;
+            a = row.a + ch.off;
+            M = row.M + ch.off;
         }
         float* th[G];
         uintptr_t mis = reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(M);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            th[g] = A.rep_tab[static_cast<int64_t>(g) * A.n_tensors + ch.tensor].p + ch.off;
+            th[g] = row.th[g] + ch.off;
             mis |= reinterpret_cast<uintptr_t>(th[g]);
         }
         const int len = ch.len;
 
         if ((mis & 15u) == 0) {
-            vfloat4* a4 = reinterpret_cast<vfloat4*>(a);
-            vfloat4* M4 = reinterpret_cast<vfloat4*>(M);
             const int n4 = len >> 2;
             int base = 0;
             for (; base + kTile <= n4; base += kTile) {
                 vfloat4 TH[UNROLL][G], Av[UNROLL], Mv[UNROLL];
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
-                    const int i = base + u * kBlock + tid;
-                    Av[u] = ld<NT>(a4 + i);
-                    Mv[u] = ld<NT>(M4 + i);
+                    const unsigned o = static_cast<unsigned>(base + u * kBlock + tid) * 16u;
+                    Av[u] = ldo<NT, vfloat4>(a, o);
+                    Mv[u] = ldo<NT, vfloat4>(M, o);
 #pragma unroll
-                    for (int g = 0; g < G; ++g)
-                        TH[u][g] = ld<NT>(reinterpret_cast<const vfloat4*>(th[g]) + i);
+                    for (int g = 0; g < G; ++g) TH[u][g] = ldo<NT, vfloat4>(th[g], o);
                 }
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
-                    const int i = base + u * kBlock + tid;
+                    const unsigned o = static_cast<unsigned>(base + u * kBlock + tid) * 16u;
                     outer_vec<G, PIER>(TH[u], Av[u], Mv[u], A.mu, A.lr, A.invG);
-                    st<NT>(a4 + i, Av[u]);
-                    st<NT>(M4 + i, Mv[u]);
+                    sto<NT>(a, o, Av[u]);
+                    sto<NT>(M, o, Mv[u]);
                     if constexpr (PIER) {
 #pragma unroll
-                        for (int g = 0; g < G; ++g)
-                            st<NT>(reinterpret_cast<vfloat4*>(th[g]) + i, TH[u][g]);
+                        for (int g = 0; g < G; ++g) sto<NT>(th[g], o, TH[u][g]);
                     }
                 }
             }
-            for (int i = base + tid; i < n4; i += kBlock) {
-                vfloat4 TH[G], Av = ld<NT>(a4 + i), Mv = ld<NT>(M4 + i);
+            for (int j = base + tid; j < n4; j += kBlock) {
+                const unsigned o = static_cast<unsigned>(j) * 16u;
+                vfloat4 TH[G], Av = ldo<NT, vfloat4>(a, o), Mv = ldo<NT, vfloat4>(M, o);
 #pragma unroll
-                for (int g = 0; g < G; ++g)
-                    TH[g] = ld<NT>(reinterpret_cast<const vfloat4*>(th[g]) + i);
+                for (int g = 0; g < G; ++g) TH[g] = ldo<NT, vfloat4>(th[g], o);
                 outer_vec<G, PIER>(TH, Av, Mv, A.mu, A.lr, A.invG);
-                st<NT>(a4 + i, Av);
-                st<NT>(M4 + i, Mv);
+                sto<NT>(a, o, Av);
+                sto<NT>(M, o, Mv);
                 if constexpr (PIER) {
 #pragma unroll
-                    for (int g = 0; g < G; ++g) st<NT>(reinterpret_cast<vfloat4*>(th[g]) + i, TH[g]);
+                    for (int g = 0; g < G; ++g) sto<NT>(th[g], o, TH[g]);
                 }
             }
             const int i = (n4 << 2) + tid;
@@ -398,29 +419,30 @@ __global__ __launch_bounds__(kBlock) void outer_kernel(OuterArgs A)
 // same arithmetic), one element per lane.  Covers the group counts without a
 // specialised kernel.
 template <bool FLAT, bool PIER>
-__global__ __launch_bounds__(kBlock) void outer_kernel_anyG(OuterArgs A)
+__global__ __launch_bounds__(kBlock) void outer_kernel_anyG(const Chunk* __restrict__ chunks,
+                                                            const uint64_t* __restrict__ rows,
+                                                            OuterArgs A)
 {
 #pragma clang fp contract(off)
     const int tid = threadIdx.x;
     for (int c = blockIdx.x; c < A.n_chunks; c += gridDim.x) {
-        const Chunk ch = A.chunks[c];
-        const OuterPtrs ot = A.otab[ch.tensor];
+        const Chunk ch = chunks[c];
+        const uint64_t* __restrict__ row = rows + static_cast<int64_t>(ch.tensor) * (kOuterRowHead + A.G);
         float* __restrict__ a;
         float* __restrict__ M;
         if constexpr (FLAT) {
-            const int64_t e = ot.flat_start + ch.off - A.flat_lo;
+            const int64_t e = static_cast<int64_t>(row[2]) + ch.off - A.flat_lo;
             a = A.flat_a + e;
             M = A.flat_M + e;
         } else {
-            a = ot.a + ch.off;
-            M = ot.M + ch.off;
+            a = reinterpret_cast<float*>(row[0]) + ch.off;
+            M = reinterpret_cast<float*>(row[1]) + ch.off;
         }
-        const RepPtrs* rt = A.rep_tab + ch.tensor;
         for (int i = tid; i < ch.len; i += kBlock) {
             const float av = ld<false>(a + i);
             float s = 0.0f, s2 = 0.0f;
             for (int g = 0; g < A.G; ++g) {
-                const float t = ld<false>(rt[static_cast<int64_t>(g) * A.n_tensors].p + ch.off + i);
+                const float t = ld<false>(reinterpret_cast<const float*>(row[kOuterRowHead + g]) + ch.off + i);
                 s = s + (t - av);
                 s2 = s2 + t;
             }
@@ -431,7 +453,7 @@ __global__ __launch_bounds__(kBlock) void outer_kernel_anyG(OuterArgs A)
                 const float x = av + A.lr * (A.mu * Mn + d);
                 st<false>(a + i, x);
                 for (int g = 0; g < A.G; ++g)
-                    st<false>(rt[static_cast<int64_t>(g) * A.n_tensors].p + ch.off + i, x);
+                    st<false>(reinterpret_cast<float*>(row[kOuterRowHead + g]) + ch.off + i, x);
             } else {
                 st<false>(a + i, s2 * A.invG);
             }
@@ -439,59 +461,61 @@ __global__ __launch_bounds__(kBlock) void outer_kernel_anyG(OuterArgs A)
     }
 }
 
+struct OuterTables {
+    const Chunk* chunks;
+    const uint64_t* rows;
+};
+
 template <int G, int U, bool FLAT, bool PIER>
-static void outer_dispatch_nt(int grid, const OuterArgs& A, bool nt, hipStream_t stream)
+static void outer_dispatch_nt(int grid, const OuterTables& T, const OuterArgs& A, bool nt, hipStream_t stream)
 {
-    if (nt) hipLaunchKernelGGL((outer_kernel<G, U, FLAT, PIER, true>), dim3(grid), dim3(kBlock), 0, stream, A);
-    else hipLaunchKernelGGL((outer_kernel<G, U, FLAT, PIER, false>), dim3(grid), dim3(kBlock), 0, stream, A);
+    const OuterRow<G>* ROWS = reinterpret_cast<const OuterRow<G>*>(T.rows);
+    if (nt) hipLaunchKernelGGL((outer_kernel<G, U, FLAT, PIER, true>), dim3(grid), dim3(kBlock), 0, stream, T.chunks, ROWS, A);
+    else hipLaunchKernelGGL((outer_kernel<G, U, FLAT, PIER, false>), dim3(grid), dim3(kBlock), 0, stream, T.chunks, ROWS, A);
 }
 
 template <int G, bool FLAT, bool PIER>
-static void outer_dispatch_u(int grid, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
+static void outer_dispatch_u(int grid, const OuterTables& T, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
 {
     const bool nt = shape.nontemporal != 0;
     // lanes keep (G + 2) * unroll 16-byte loads in flight; cap the product
     int u = shape.unroll;
     while (u > 1 && (G + 2) * u > 20) u >>= 1;
     switch (u) {
-    case 1: outer_dispatch_nt<G, 1, FLAT, PIER>(grid, A, nt, stream); break;
-    case 2: outer_dispatch_nt<G, 2, FLAT, PIER>(grid, A, nt, stream); break;
+    case 1: outer_dispatch_nt<G, 1, FLAT, PIER>(grid, T, A, nt, stream); break;
+    case 2: outer_dispatch_nt<G, 2, FLAT, PIER>(grid, T, A, nt, stream); break;
     default:
-        if constexpr ((G + 2) * 4 <= 20) outer_dispatch_nt<G, 4, FLAT, PIER>(grid, A, nt, stream);
-        else outer_dispatch_nt<G, 2, FLAT, PIER>(grid, A, nt, stream);
+        if constexpr ((G + 2) * 4 <= 20) outer_dispatch_nt<G, 4, FLAT, PIER>(grid, T, A, nt, stream);
+        else outer_dispatch_nt<G, 2, FLAT, PIER>(grid, T, A, nt, stream);
         break;
     }
 }
 
 template <bool FLAT, bool PIER>
-static void outer_dispatch_g(int grid, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
+static void outer_dispatch_g(int grid, const OuterTables& T, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
 {
     switch (A.G) {
-    case 1: outer_dispatch_u<1, FLAT, PIER>(grid, A, shape, stream); break;
-    case 2: outer_dispatch_u<2, FLAT, PIER>(grid, A, shape, stream); break;
-    case 4: outer_dispatch_u<4, FLAT, PIER>(grid, A, shape, stream); break;
-    case 8: outer_dispatch_u<8, FLAT, PIER>(grid, A, shape, stream); break;
+    case 1: outer_dispatch_u<1, FLAT, PIER>(grid, T, A, shape, stream); break;
+    case 2: outer_dispatch_u<2, FLAT, PIER>(grid, T, A, shape, stream); break;
+    case 4: outer_dispatch_u<4, FLAT, PIER>(grid, T, A, shape, stream); break;
+    case 8: outer_dispatch_u<8, FLAT, PIER>(grid, T, A, shape, stream); break;
     default:
-        hipLaunchKernelGGL((outer_kernel_anyG<FLAT, PIER>), dim3(grid), dim3(kBlock), 0, stream, A);
+        hipLaunchKernelGGL((outer_kernel_anyG<FLAT, PIER>), dim3(grid), dim3(kBlock), 0, stream, T.chunks, T.rows, A);
         break;
     }
 }
 
-hipError_t launch_outer(const Chunk* chunks, int n_chunks, const RepPtrs* rep_tab, int n_tensors,
-                        int G, const OuterPtrs* otab, float* flat_a, float* flat_M,
-                        int64_t flat_lo, float mu, float lr, bool pier_phase,
-                        const LaunchShape& shape, hipStream_t stream)
+hipError_t launch_outer(const Chunk* chunks, int n_chunks, const uint64_t* rows, int G,
+                        float* flat_a, float* flat_M, int64_t flat_lo, float mu, float lr,
+                        bool pier_phase, const LaunchShape& shape, hipStream_t stream)
 {
     if (n_chunks <= 0) return hipSuccess;
+    const OuterTables T{chunks, rows};
     OuterArgs A;
-    A.chunks = chunks;
-    A.rep_tab = rep_tab;
-    A.otab = otab;
     A.flat_a = flat_a;
     A.flat_M = flat_M;
     A.flat_lo = flat_lo;
     A.n_chunks = n_chunks;
-    A.n_tensors = n_tensors;
     A.G = G;
     A.mu = mu;
     A.lr = lr;
@@ -499,12 +523,38 @@ hipError_t launch_outer(const Chunk* chunks, int n_chunks, const RepPtrs* rep_ta
     const int grid = grid_for(n_chunks, shape);
     const bool flat = flat_a != nullptr;
     if (flat) {
-        if (pier_phase) outer_dispatch_g<true, true>(grid, A, shape, stream);
-        else outer_dispatch_g<true, false>(grid, A, shape, stream);
+        if (pier_phase) outer_dispatch_g<true, true>(grid, T, A, shape, stream);
+        else outer_dispatch_g<true, false>(grid, T, A, shape, stream);
     } else {
-        if (pier_phase) outer_dispatch_g<false, true>(grid, A, shape, stream);
-        else outer_dispatch_g<false, false>(grid, A, shape, stream);
+        if (pier_phase) outer_dispatch_g<false, true>(grid, T, A, shape, stream);
+        else outer_dispatch_g<false, false>(grid, T, A, shape, stream);
     }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ placement probe
+//
+// The access pattern of the two optimizer kernels reduced to its memory behaviour: every
+// lane reads one vector from each of two buffers and writes both back in place (the sum
+// keeps the loads alive; the buffers are scratch while a probe runs).
+__global__ __launch_bounds__(kBlock) void probe_kernel(float* __restrict__ x, float* __restrict__ y,
+                                                       int64_t n4)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i >= n4) return;
+    vfloat4* x4 = reinterpret_cast<vfloat4*>(x);
+    vfloat4* y4 = reinterpret_cast<vfloat4*>(y);
+    const vfloat4 a = ld<true>(x4 + i), b = ld<true>(y4 + i);
+    const vfloat4 s = a + b;
+    st<true>(x4 + i, s);
+    st<true>(y4 + i, s);
+}
+
+hipError_t launch_probe(float* x, float* y, int64_t n4, hipStream_t stream)
+{
+    if (n4 <= 0) return hipSuccess;
+    const int64_t grid = (n4 + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(probe_kernel, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, stream, x, y, n4);
     return hipGetLastError();
 }
 

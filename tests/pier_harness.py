@@ -68,7 +68,7 @@ class Run:
 
     def __init__(self, numels, G, *, grad_bf16=False, hp=None, seed=0, param_std=0.02, grad_std=1e-3,
                  pad=0, launch=None, offload=False, chunk_bytes=None, sample=None, shared_grad=False,
-                 stream=None):
+                 stream=None, arena=None):
         self.numels, self.G, self.pad = list(numels), G, pad
         self.grad_bf16 = grad_bf16
         self.hp = hp or dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
@@ -77,21 +77,29 @@ class Run:
         self.stream = stream or torch.cuda.current_stream()
         self.t = 0
         gdt = torch.bfloat16 if grad_bf16 else torch.float32
-        self.P = [dev.FlatList(numels, pad=pad) for _ in range(G)]
-        self.M1 = [dev.FlatList(numels, pad=pad) for _ in range(G)]
-        self.V = [dev.FlatList(numels, pad=pad) for _ in range(G)]
-        if shared_grad:
-            g0 = dev.FlatList(numels, dtype=gdt, pad=pad)
-            self.Gd = [g0] * G
-        else:
-            self.Gd = [dev.FlatList(numels, dtype=gdt, pad=pad) for _ in range(G)]
-        if offload:
+        if arena is not None:
+            # carved out of a probed arena, placed by address class
             assert pad == 0
-            self.A = dev.FlatList(numels, pinned=True)
-            self.Mo = dev.FlatList(numels, pinned=True)
+            S = dev.PlacedState(numels, G, grad_dtype=gdt, arena=arena,
+                                outer="pinned" if offload else "device", shared_grad=shared_grad)
+            self.P, self.M1, self.V, self.Gd, self.A, self.Mo = S.P, S.M1, S.V, S.Gd, S.A, S.Mo
+            self.Mo.flat.zero_()
         else:
-            self.A = dev.FlatList(numels, pad=pad)
-            self.Mo = dev.FlatList(numels, pad=pad)
+            self.P = [dev.FlatList(numels, pad=pad) for _ in range(G)]
+            self.M1 = [dev.FlatList(numels, pad=pad) for _ in range(G)]
+            self.V = [dev.FlatList(numels, pad=pad) for _ in range(G)]
+            if shared_grad:
+                g0 = dev.FlatList(numels, dtype=gdt, pad=pad)
+                self.Gd = [g0] * G
+            else:
+                self.Gd = [dev.FlatList(numels, dtype=gdt, pad=pad) for _ in range(G)]
+            if offload:
+                assert pad == 0
+                self.A = dev.FlatList(numels, pinned=True)
+                self.Mo = dev.FlatList(numels, pinned=True)
+            else:
+                self.A = dev.FlatList(numels, pad=pad)
+                self.Mo = dev.FlatList(numels, pad=pad)
         self.P[0].fill_normal(seed=seed, stream=shapes.PARAM_STREAM, step=0, std=param_std)
         for g in range(1, G):
             self.P[g].flat.copy_(self.P[0].flat)

@@ -1,4 +1,7 @@
-"""GPU parity at the full sizes of the benchmark configurations, in the launch
+"""(Collected after the small-case file on purpose: these cases hold ~210 GB of HBM and
+64 GiB of pinned host memory, so they run when nothing else is left to run.)
+
+GPU parity at the full sizes of the benchmark configurations, in the launch
 configuration bench.py times (library defaults), on a deterministic sample of element
 indices: a strided sweep of 2^16 positions plus the first/last elements of every tensor
 and the neighbourhood of chunk and offload-piece boundaries.  The update is
@@ -19,8 +22,12 @@ def _log(msg):
 
 
 def _free():
+    """Return device memory and the cached pinned host blocks (2 x 32 GiB after the 7B case)."""
     gc.collect()
     torch.cuda.empty_cache()
+    host_empty = getattr(torch._C, "_host_emptyCache", None)
+    if host_empty is not None:
+        host_empty()
 
 
 def _scalars(t, T, fixed):
@@ -37,7 +44,17 @@ def _scalars(t, T, fixed):
     return ph, mu, lr
 
 
-def _run_config(name, chunk_bytes=None, expect_phases=None):
+def _arena():
+    """The probed HBM arena bench.py places the big configurations in."""
+    import paper_2511_17849_amd as pier
+    _free()
+    free, _ = torch.cuda.mem_get_info()
+    a = pier.HbmArena(free - (8 << 30))
+    _log("arena %.0f GiB, classes %s" % (a.buf.numel() / 2 ** 30, "".join(str(c) for c in a.classes)))
+    return a
+
+
+def _run_config(name, chunk_bytes=None, expect_phases=None, arena=None):
     import pier_harness as H_
     from pier_inputs import shapes
     w = shapes.workloads()[name]
@@ -46,7 +63,7 @@ def _run_config(name, chunk_bytes=None, expect_phases=None):
     _log("%s: N=%d G=%d H=%d rounds=%d sampled=%d" % (name, w.N, w.G, w.H, w.rounds, idx.size))
     hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay)
     r = H_.Run(w.numels, w.G, grad_bf16=w.grad_bf16, hp=hp, seed=w.seed, param_std=w.param_std,
-               grad_std=w.grad_std, offload=w.offload, chunk_bytes=chunk_bytes, sample=idx)
+               grad_std=w.grad_std, offload=w.offload, chunk_bytes=chunk_bytes, sample=idx, arena=arena)
     phases = []
     try:
         for k in range(w.rounds):
@@ -93,6 +110,25 @@ def test_config4_gpt2_xl_resident():
     _free()
 
 
+@pytest.mark.timeout(600)
+def test_config4_gpt2_xl_in_probed_arena():
+    arena = _arena()
+    r, rep = _run_config("gpt2_xl", arena=arena)
+    # placement policy: theta_g and m_g share an address class, v_g and grad_g share another
+    # (first-fit may have to deviate for a replica or two when a class runs out of room)
+    if arena.n_classes >= 2:
+        ok = sum(1 for g in range(8) if r.P[g].cls == r.M1[g].cls and r.V[g].cls == r.Gd[g].cls
+                 and r.V[g].cls != r.P[g].cls)
+        assert ok >= 6, [(r.P[g].cls, r.M1[g].cls, r.V[g].cls, r.Gd[g].cls) for g in range(8)]
+        assert len({r.P[g].cls for g in range(8)}) == arena.n_classes or arena.n_classes > 3
+    del r, arena
+    _free()
+
+
+# Last on purpose.  With this case earlier in the process (64 GiB of pinned host memory and
+# 215 GB of HBM allocated and released), a later, unrelated small offload case took a host-side
+# segmentation fault when it first touched freshly created torch side streams; the cause was
+# not established, so nothing runs after this case and its pinned blocks are released.
 @pytest.mark.timeout(900)
 def test_config5_gpt_7b_host_offload_256mib_pieces():
     r, rep = _run_config("gpt_7b", chunk_bytes=256 << 20)
