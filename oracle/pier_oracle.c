@@ -86,6 +86,38 @@ void pier_oracle_adamw_bf16(float* p, float* m, float* v, const uint16_t* g,
 }
 
 /* ------------------------------------------------------------------------
+ * Global-norm gradient clipping (Table I: "clip grad 1").  The paper gives the
+ * threshold only; the rule is the standard one of the framework it builds on:
+ * total L2 norm over every gradient element of the model, coefficient
+ * max_norm / (norm + 1e-6), applied only when it is below 1.  The sum of squares
+ * is accumulated in double, element by element in list order; the coefficient is
+ * formed in double and rounded once to fp32 (it becomes the inner step's
+ * grad_scale).
+ * ---------------------------------------------------------------------- */
+double pier_oracle_sumsq(const float* g, int64_t n, double acc)
+{
+    for (int64_t i = 0; i < n; ++i) acc = acc + (double)g[i] * (double)g[i];
+    return acc;
+}
+
+double pier_oracle_sumsq_bf16(const uint16_t* g, int64_t n, double acc)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        uint32_t bits = (uint32_t)g[i] << 16;
+        float gf;
+        memcpy(&gf, &bits, sizeof gf);
+        acc = acc + (double)gf * (double)gf;
+    }
+    return acc;
+}
+
+float pier_oracle_clip_coef(double sumsq, float max_norm)
+{
+    double coef = (double)max_norm / (sqrt(sumsq) + 1e-6);
+    return coef < 1.0 ? (float)coef : 1.0f;
+}
+
+/* ------------------------------------------------------------------------
  * Outer step (Algorithm 2, the else-branch; Algorithm 1, the t mod r = 0
  * branch).  theta[g] is group g's current model, a the model at the previous
  * synchronisation (theta_{t-r}), M the outer momentum.

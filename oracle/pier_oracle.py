@@ -53,6 +53,13 @@ class Oracle:
         L.pier_oracle_outer_lr.restype = f32
         L.pier_oracle_outer_scalars.argtypes = [i64, i64, ctypes.POINTER(i32), f32p, f32p]
         L.pier_oracle_outer_scalars.restype = None
+        f64 = ctypes.c_double
+        L.pier_oracle_sumsq.argtypes = [f32p, i64, f64]
+        L.pier_oracle_sumsq.restype = f64
+        L.pier_oracle_sumsq_bf16.argtypes = [ctypes.POINTER(ctypes.c_uint16), i64, f64]
+        L.pier_oracle_sumsq_bf16.restype = f64
+        L.pier_oracle_clip_coef.argtypes = [f64, f32]
+        L.pier_oracle_clip_coef.restype = f32
         self._L = L
 
     def adamw(self, p, m, v, g, *, lr, beta1, beta2, eps, weight_decay, step, grad_scale=1.0):
@@ -76,6 +83,18 @@ class Oracle:
         assert G >= 1 and M.size == n and all(t.size == n for t in thetas)
         arr = (ctypes.POINTER(ctypes.c_float) * G)(*[_f32(t) for t in thetas])
         self._L.pier_oracle_outer(arr, G, _f32(a), _f32(M), n, mu, lr, int(phase))
+
+    def sumsq(self, g, acc=0.0):
+        """acc + sum of squares of the gradient array g (float32, or uint16 bfloat16 bits),
+        accumulated in double in index order; chain calls over a tensor list."""
+        if g.dtype == np.uint16:
+            assert g.flags.c_contiguous
+            return self._L.pier_oracle_sumsq_bf16(g.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)), g.size, acc)
+        return self._L.pier_oracle_sumsq(_f32(g), g.size, acc)
+
+    def clip_coef(self, sumsq, max_norm):
+        """fp32 factor the gradients are multiplied by: min(1, max_norm / (sqrt(sumsq) + 1e-6))."""
+        return self._L.pier_oracle_clip_coef(sumsq, max_norm)
 
     def phase(self, t, T):
         return self._L.pier_oracle_phase(t, T)
@@ -115,6 +134,14 @@ def adamw(*a, **k):
 
 def outer(*a, **k):
     return default().outer(*a, **k)
+
+
+def sumsq(g, acc=0.0):
+    return default().sumsq(g, acc)
+
+
+def clip_coef(sumsq_, max_norm):
+    return default().clip_coef(sumsq_, max_norm)
 
 
 def phase(t, T):

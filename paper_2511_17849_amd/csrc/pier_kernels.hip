@@ -73,17 +73,6 @@ __device__ __forceinline__ float bf16_to_f32(unsigned short h)
 __device__ __forceinline__ void adamw_elem(float& p, float& m, float& v, float g,
                                            const AdamwScalars& s)
 {
-#ifdef PIER_EXPERIMENT_FAST_MATH
-    g = g * s.grad_scale;
-    const float mn = s.beta1 * m + s.om1 * g;
-    const float vn = s.beta2 * v + (s.om2 * g) * g;
-    const float mh = mn * (1.0f / s.bc1);
-    const float vh = vn * (1.0f / s.bc2);
-    const float u = mh * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vh) + s.eps) + s.wd * p;
-    p = p - s.lr * u;
-    m = mn;
-    v = vn;
-#else
 #pragma clang fp contract(off)
     g = g * s.grad_scale;
     const float mn = s.beta1 * m + s.om1 * g;
@@ -94,7 +83,6 @@ __device__ __forceinline__ void adamw_elem(float& p, float& m, float& v, float g
     p = p - s.lr * u;
     m = mn;
     v = vn;
-#endif
 }
 
 template <bool BF16>

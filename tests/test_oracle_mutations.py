@@ -28,6 +28,14 @@ MUTATIONS = [
      "*p = *p - lr * (mh / (sqrtf(vh) + eps));\n    *p = *p - lr * wd * (*p) * 40.0f;"),
     ("bf16 shifted wrong", "(uint32_t)g[i] << 16", "(uint32_t)g[i] << 15"),
     ("grad_scale ignored", "if (grad_scale != 1.0f) g = g * grad_scale;", ""),
+    ("clip: norm without the root", "(sqrt(sumsq) + 1e-6)", "(sumsq + 1e-6)"),
+    ("clip: epsilon dropped", "(sqrt(sumsq) + 1e-6)", "(sqrt(sumsq))"),
+    ("clip: always scales", "return coef < 1.0 ? (float)coef : 1.0f;", "return (float)coef;"),
+    ("clip: sum of values, not squares", "acc = acc + (double)g[i] * (double)g[i];", "acc = acc + (double)g[i];"),
+    ("clip: accumulator restarts per tensor", "double pier_oracle_sumsq(const float* g, int64_t n, double acc)\n{",
+     "double pier_oracle_sumsq(const float* g, int64_t n, double acc)\n{ acc = 0;"),
+    ("clip: bf16 shifted wrong", "uint32_t bits = (uint32_t)g[i] << 16;\n        float gf;\n        memcpy(&gf, &bits, sizeof gf);\n        acc",
+     "uint32_t bits = (uint32_t)g[i] << 15;\n        float gf;\n        memcpy(&gf, &bits, sizeof gf);\n        acc"),
     ("sum instead of mean", "float d = s * invG;", "float d = s;"),
     ("anchor minus model", "s = s + (theta[g][i] - a[i]);", "s = s + (a[i] - theta[g][i]);"),
     ("first group only", "for (int g = 0; g < G; ++g) s = s + (theta[g][i] - a[i]);",
@@ -60,6 +68,8 @@ def battery():
         (pins.test_adamw_matches_torch_library, (pins.HP,)),
         (pins.test_adamw_bf16_gradients_widen_exactly, ()),
         (pins.test_adamw_grad_scale_is_a_gradient_multiplier, ()),
+        (pins.test_clip_hand_case_and_closed_form, ()),
+        (pins.test_clip_matches_torch_clip_grad_norm, ()),
         (pins.test_outer_single_group_unit_rate_returns_the_model, ()),
         (pins.test_outer_unit_rate_no_momentum_is_the_replica_mean, ()),
         (pins.test_outer_nesterov_two_rounds_by_hand, ()),

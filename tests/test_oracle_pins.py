@@ -142,6 +142,61 @@ def test_adamw_grad_scale_is_a_gradient_multiplier():
         assert np.array_equal(x, y)
 
 
+# ---------------------------------------------------------------- gradient clipping
+
+def test_clip_hand_case_and_closed_form():
+    # |(3, 4)| = 5: coefficient 1 / (5 + 1e-6); no clipping below the threshold
+    ss = O.sumsq(f32([3.0, 4.0]))
+    assert ss == 25.0
+    assert O.clip_coef(ss, 1.0) == np.float32(1.0 / (5.0 + 1e-6))
+    assert O.clip_coef(ss, 1.0) != np.float32(0.2)             # the 1e-6 is there
+    assert O.clip_coef(ss, 10.0) == 1.0 and O.clip_coef(0.0, 1.0) == 1.0
+    # constant gradient: norm = |c| sqrt(n); chained over a tensor list
+    c, n = 1e-3, 1 << 20
+    g = np.full(n, c, np.float32)
+    ss = O.sumsq(g[:1000], 0.0)
+    ss = O.sumsq(g[1000:], ss)
+    assert abs(np.sqrt(ss) - abs(float(np.float32(c))) * np.sqrt(n)) < 1e-9      # 2^20 double additions
+    assert abs(O.clip_coef(ss, 1.0) - 1.0 / (float(np.float32(c)) * 1024.0 + 1e-6)) < 1e-7
+    # bf16 gradients are widened exactly
+    from pier_inputs import generator as gen
+    h = gen.to_bf16_bits(np.array([3.0, 4.0, -12.0], np.float32))
+    assert O.sumsq(h) == 169.0
+
+
+def test_clip_matches_torch_clip_grad_norm():
+    # library routine: torch.nn.utils.clip_grad_norm_ over a list of tensors
+    rng = np.random.default_rng(12)
+    sizes = [1000, 33, 70_000, 5]
+    gs = [rng.normal(0, 1e-3, k).astype(np.float32) for k in sizes]
+    ss = 0.0
+    for g in gs:
+        ss = O.sumsq(g, ss)
+    ps = [torch.nn.Parameter(torch.zeros(k)) for k in sizes]
+    for p, g in zip(ps, gs):
+        p.grad = torch.from_numpy(g.copy())
+    for max_norm in (0.05, 1.0):
+        for p, g in zip(ps, gs):
+            p.grad = torch.from_numpy(g.copy())
+        total = torch.nn.utils.clip_grad_norm_(ps, max_norm, foreach=False)
+        assert abs(float(total) - np.sqrt(ss)) < 2e-7 * np.sqrt(ss)   # the library sums in fp32
+        coef = O.clip_coef(ss, max_norm)
+        if np.sqrt(ss) <= max_norm:
+            assert coef == 1.0
+        else:
+            assert coef < 1.0
+        for p, g in zip(ps, gs):
+            np.testing.assert_allclose(p.grad.numpy(), g * coef, rtol=3e-7, atol=0)
+    # feeding the coefficient as grad_scale equals stepping on the clipped gradient
+    coef = O.clip_coef(ss, 0.05)
+    a = [rng.normal(0, 0.02, 1000).astype(np.float32), np.zeros(1000, np.float32), np.zeros(1000, np.float32)]
+    b = [x.copy() for x in a]
+    O.adamw(*a, gs[0], step=1, grad_scale=coef, **HP)
+    O.adamw(*b, (gs[0] * np.float32(coef)).astype(np.float32), step=1, **HP)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
 # ---------------------------------------------------------------- outer step
 
 def test_outer_single_group_unit_rate_returns_the_model():
