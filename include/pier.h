@@ -115,6 +115,20 @@ typedef struct {
 } pier_adamw_hp;
 pier_status pier_inner_adamw(pier_ctx* ctx, int replica, const pier_adamw_hp* hp, void* hip_stream);
 
+/* The same step preceded by global-norm gradient clipping (Table I: "clip grad 1"; the
+ * paper names the threshold, the rule is the usual one): over all gradient elements of
+ * the replica, norm = sqrt(sum g^2) accumulated in double, coefficient
+ * c = min(1, max_norm / (norm + 1e-6)) rounded to fp32, and the step runs with every
+ * gradient element multiplied by grad_scale * c.  Three launches on hip_stream (partial
+ * sums, fold, AdamW), no host synchronisation; the gradient is read twice (32 B/param).
+ * The fold uses a fixed order, so the norm is the same in every run. */
+pier_status pier_inner_adamw_clipped(pier_ctx* ctx, int replica, const pier_adamw_hp* hp,
+                                     float max_norm, void* hip_stream);
+/* Norm and coefficient computed by the replica's most recent clipped step: waits for
+ * hip_stream, then copies them to the host (either output may be NULL). */
+pier_status pier_grad_norm_last(pier_ctx* ctx, int replica, double* norm_out, float* coef_out,
+                                void* hip_stream);
+
 /* ----------------------------------------------------------- outer step
  * Algorithm 2's synchronisation branch (PIER) and Algorithm 1's (WARMUP), fused
  * into one kernel over all replicas, with anchor and M on the device:

@@ -65,6 +65,8 @@ def _load():
         "pier_bind_replica": (i32, [vp, i32, pp, pp, pp, pp, i32]),
         "pier_bind_outer": (i32, [vp, i32, pp, pp]),
         "pier_inner_adamw": (i32, [vp, i32, ctypes.POINTER(AdamwHP), vp]),
+        "pier_inner_adamw_clipped": (i32, [vp, i32, ctypes.POINTER(AdamwHP), f32, vp]),
+        "pier_grad_norm_last": (i32, [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(f32), vp]),
         "pier_outer_step": (i32, [vp, ctypes.POINTER(OuterHP), vp]),
         "pier_offload_workspace_bytes": (i32, [vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]),
         "pier_offload_stream": (i32, [vp, ctypes.POINTER(OuterHP), ctypes.c_size_t, vp, ctypes.c_size_t,
@@ -171,6 +173,21 @@ def pier_inner_adamw(ctx, replica, *, lr, beta1, beta2, eps, weight_decay, step,
                      stream=None):
     hp = AdamwHP(lr, beta1, beta2, eps, weight_decay, grad_scale, int(step))
     _check(_load().pier_inner_adamw(ctx.handle, int(replica), ctypes.byref(hp), _stream(stream)))
+
+
+def pier_inner_adamw_clipped(ctx, replica, *, lr, beta1, beta2, eps, weight_decay, step, max_norm,
+                             grad_scale=1.0, stream=None):
+    hp = AdamwHP(lr, beta1, beta2, eps, weight_decay, grad_scale, int(step))
+    _check(_load().pier_inner_adamw_clipped(ctx.handle, int(replica), ctypes.byref(hp), max_norm,
+                                            _stream(stream)))
+
+
+def pier_grad_norm_last(ctx, replica, stream=None):
+    """(norm, coefficient) of the replica's latest clipped step; synchronises the stream."""
+    norm, coef = ctypes.c_double(), ctypes.c_float()
+    _check(_load().pier_grad_norm_last(ctx.handle, int(replica), ctypes.byref(norm), ctypes.byref(coef),
+                                       _stream(stream)))
+    return norm.value, coef.value
 
 
 def pier_outer_step(ctx, *, outer_lr, mu, phase, stream=None):

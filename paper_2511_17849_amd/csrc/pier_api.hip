@@ -75,6 +75,10 @@ struct pier_ctx {
     std::vector<char> rep_bound;
     std::vector<char> rep_bf16;
 
+    double* d_partials = nullptr;  // n_replicas * kMaxNormPartials partial sums of the norm pass
+    ClipState* d_clip = nullptr;   // one per replica
+    std::vector<char> clip_valid;
+
     std::vector<uint64_t> h_rows;  // n_tensors rows of outer_row_words(n_replicas) words
     uint64_t* d_rows = nullptr;
     bool outer_bound = false;
@@ -134,6 +138,10 @@ pier_status ensure_device(pier_ctx* c)
     PIER_HIP(hipMalloc(reinterpret_cast<void**>(&c->d_rows), sizeof(uint64_t) * c->h_rows.size()));
     PIER_HIP(hipMemcpy(c->d_rows, c->h_rows.data(), sizeof(uint64_t) * c->h_rows.size(),
                        hipMemcpyHostToDevice));
+    PIER_HIP(hipMalloc(reinterpret_cast<void**>(&c->d_partials),
+                       sizeof(double) * kMaxNormPartials * c->n_replicas));
+    PIER_HIP(hipMalloc(reinterpret_cast<void**>(&c->d_clip), sizeof(ClipState) * c->n_replicas));
+    PIER_HIP(hipMemset(c->d_clip, 0, sizeof(ClipState) * c->n_replicas));
     PIER_HIP(hipEventCreate(&c->offload_done));
     c->device = dev;
     return PIER_OK;
@@ -252,6 +260,7 @@ pier_status pier_ctx_create(pier_ctx** out, int n_tensors, const int64_t* numel,
         c->h_rep.assign(static_cast<size_t>(n_replicas) * n_tensors, RepPtrs{});
         c->rep_bound.assign(n_replicas, 0);
         c->rep_bf16.assign(n_replicas, 0);
+        c->clip_valid.assign(n_replicas, 0);
         const size_t rw = outer_row_words(n_replicas);
         c->h_rows.assign(rw * n_tensors, 0);
         for (int i = 0; i < n_tensors; ++i) c->h_rows[rw * i + 2] = static_cast<uint64_t>(c->flat_start[i]);
@@ -270,6 +279,8 @@ pier_status pier_ctx_destroy(pier_ctx* c)
         if (c->d_chunks) (void)hipFree(c->d_chunks);
         if (c->d_rep) (void)hipFree(c->d_rep);
         if (c->d_rows) (void)hipFree(c->d_rows);
+        if (c->d_partials) (void)hipFree(c->d_partials);
+        if (c->d_clip) (void)hipFree(c->d_clip);
         for (auto& kv : c->plans) free_plan(kv.second);
         if (c->offload_done) (void)hipEventDestroy(c->offload_done);
     }
@@ -377,7 +388,8 @@ pier_status pier_bind_outer(pier_ctx* c, pier_loc loc, float* const* anchor,
     return PIER_OK;
 }
 
-pier_status pier_inner_adamw(pier_ctx* c, int replica, const pier_adamw_hp* hp, void* hip_stream)
+static pier_status inner_adamw_impl(pier_ctx* c, int replica, const pier_adamw_hp* hp, bool clip,
+                                    float max_norm, void* hip_stream)
 {
     if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
     if (!hp) return fail(PIER_ERR_INVALID_ARG, "hp is NULL");
@@ -390,6 +402,8 @@ pier_status pier_inner_adamw(pier_ctx* c, int replica, const pier_adamw_hp* hp, 
     if (!std::isfinite(hp->lr) || !std::isfinite(hp->eps) || !std::isfinite(hp->weight_decay) ||
         !std::isfinite(hp->grad_scale) || hp->eps < 0.0f)
         return fail(PIER_ERR_INVALID_ARG, "lr / eps / weight_decay / grad_scale not finite, or eps < 0");
+    if (clip && !(max_norm > 0.0f && std::isfinite(max_norm)))
+        return fail(PIER_ERR_INVALID_ARG, "max_norm = %g, need a positive finite value", static_cast<double>(max_norm));
     pier_status st = ensure_device(c);
     if (st != PIER_OK) return st;
 
@@ -405,9 +419,47 @@ pier_status pier_inner_adamw(pier_ctx* c, int replica, const pier_adamw_hp* hp, 
     s.bc1 = static_cast<float>(1.0 - std::pow(static_cast<double>(hp->beta1), static_cast<double>(hp->step)));
     s.bc2 = static_cast<float>(1.0 - std::pow(static_cast<double>(hp->beta2), static_cast<double>(hp->step)));
     s.grad_scale = hp->grad_scale;
-    PIER_HIP(launch_adamw(c->d_chunks, c->n_chunks,
-                          c->d_rep + static_cast<size_t>(replica) * c->n_tensors,
-                          c->rep_bf16[replica] != 0, s, c->shape, static_cast<hipStream_t>(hip_stream)));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const RepPtrs* tab = c->d_rep + static_cast<size_t>(replica) * c->n_tensors;
+    const ClipState* cs = nullptr;
+    if (clip) {
+        PIER_HIP(launch_grad_norm(c->d_chunks, c->n_chunks, tab, c->rep_bf16[replica] != 0,
+                                  c->d_partials + static_cast<size_t>(replica) * kMaxNormPartials,
+                                  kMaxNormPartials, max_norm, c->d_clip + replica, stream));
+        c->clip_valid[replica] = 1;
+        cs = c->d_clip + replica;
+    }
+    PIER_HIP(launch_adamw(c->d_chunks, c->n_chunks, tab, c->rep_bf16[replica] != 0, s, cs, c->shape, stream));
+    return PIER_OK;
+}
+
+pier_status pier_inner_adamw(pier_ctx* c, int replica, const pier_adamw_hp* hp, void* hip_stream)
+{
+    return inner_adamw_impl(c, replica, hp, false, 0.0f, hip_stream);
+}
+
+pier_status pier_inner_adamw_clipped(pier_ctx* c, int replica, const pier_adamw_hp* hp, float max_norm,
+                                     void* hip_stream)
+{
+    return inner_adamw_impl(c, replica, hp, true, max_norm, hip_stream);
+}
+
+pier_status pier_grad_norm_last(pier_ctx* c, int replica, double* norm_out, float* coef_out,
+                                void* hip_stream)
+{
+    if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
+    if (replica < 0 || replica >= c->n_replicas)
+        return fail(PIER_ERR_INVALID_ARG, "replica = %d, context has %d", replica, c->n_replicas);
+    if (c->device < 0 || !c->clip_valid[replica])
+        return fail(PIER_ERR_STATE, "replica %d has not run a clipped step", replica);
+    pier_status st = ensure_device(c);
+    if (st != PIER_OK) return st;
+    ClipState h;
+    PIER_HIP(hipMemcpyAsync(&h, c->d_clip + replica, sizeof h, hipMemcpyDeviceToHost,
+                            static_cast<hipStream_t>(hip_stream)));
+    PIER_HIP(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
+    if (norm_out) *norm_out = h.norm;
+    if (coef_out) *coef_out = h.coef;
     return PIER_OK;
 }
 

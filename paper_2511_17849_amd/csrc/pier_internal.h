@@ -45,8 +45,26 @@ struct LaunchShape {
 
 constexpr int kBlock = 256;  // four 64-wide wavefronts
 
+// Result of the gradient-norm pass of one replica (device memory).
+struct ClipState {
+    double sumsq;  // sum of squares of every gradient element
+    double norm;   // its square root
+    float coef;    // min(1, max_norm / (norm + 1e-6))
+    float reserved;
+};
+
+constexpr int kMaxNormPartials = 16384;  // workgroups (= partial sums) of the norm pass
+
+// clip: nullptr, or the replica's ClipState whose coef multiplies grad_scale.
 hipError_t launch_adamw(const Chunk* chunks, int n_chunks, const RepPtrs* tab, bool grad_bf16,
-                        const AdamwScalars& s, const LaunchShape& shape, hipStream_t stream);
+                        const AdamwScalars& s, const ClipState* clip, const LaunchShape& shape,
+                        hipStream_t stream);
+
+// Sum of squares of a replica's gradients: n_partials (<= kMaxNormPartials) workgroups
+// write one double each, then one workgroup folds them and the clip coefficient into *out.
+hipError_t launch_grad_norm(const Chunk* chunks, int n_chunks, const RepPtrs* tab, bool grad_bf16,
+                            double* partials, int n_partials, float max_norm, ClipState* out,
+                            hipStream_t stream);
 
 // rows: n_tensors rows of outer_row_words(G) words.  When flat_a != nullptr the anchor
 // and momentum of element e of the flat index space are flat_a[e - flat_lo] and

@@ -135,8 +135,11 @@ template <int UNROLL, bool BF16, bool NT>
 __global__ __launch_bounds__(kBlock) void adamw_kernel(const Chunk* __restrict__ chunks,
                                                        int n_chunks,
                                                        const RepPtrs* __restrict__ tab,
+                                                       const ClipState* __restrict__ clip,
                                                        AdamwScalars s)
 {
+    // gradient clipping: the coefficient of the norm pass that ran before this launch
+    if (clip) s.grad_scale = s.grad_scale * clip->coef;
     typedef typename GradVec<BF16>::type gvec;
     typedef typename std::conditional<BF16, unsigned short, float>::type gscalar;
     const int tid = threadIdx.x;
@@ -206,33 +209,139 @@ static int grid_for(int n_chunks, const LaunchShape& shape)
 
 template <int U, bool BF16>
 static void adamw_dispatch_nt(int grid, const Chunk* chunks, int n_chunks, const RepPtrs* tab,
-                              const AdamwScalars& s, bool nt, hipStream_t stream)
+                              const ClipState* clip, const AdamwScalars& s, bool nt, hipStream_t stream)
 {
     if (nt) hipLaunchKernelGGL((adamw_kernel<U, BF16, true>), dim3(grid), dim3(kBlock), 0, stream,
-                               chunks, n_chunks, tab, s);
+                               chunks, n_chunks, tab, clip, s);
     else hipLaunchKernelGGL((adamw_kernel<U, BF16, false>), dim3(grid), dim3(kBlock), 0, stream,
-                            chunks, n_chunks, tab, s);
+                            chunks, n_chunks, tab, clip, s);
 }
 
 template <bool BF16>
 static void adamw_dispatch_u(int grid, const Chunk* chunks, int n_chunks, const RepPtrs* tab,
-                             const AdamwScalars& s, const LaunchShape& shape, hipStream_t stream)
+                             const ClipState* clip, const AdamwScalars& s, const LaunchShape& shape,
+                             hipStream_t stream)
 {
     const bool nt = shape.nontemporal != 0;
     switch (shape.unroll) {
-    case 1: adamw_dispatch_nt<1, BF16>(grid, chunks, n_chunks, tab, s, nt, stream); break;
-    case 2: adamw_dispatch_nt<2, BF16>(grid, chunks, n_chunks, tab, s, nt, stream); break;
-    default: adamw_dispatch_nt<4, BF16>(grid, chunks, n_chunks, tab, s, nt, stream); break;
+    case 1: adamw_dispatch_nt<1, BF16>(grid, chunks, n_chunks, tab, clip, s, nt, stream); break;
+    case 2: adamw_dispatch_nt<2, BF16>(grid, chunks, n_chunks, tab, clip, s, nt, stream); break;
+    default: adamw_dispatch_nt<4, BF16>(grid, chunks, n_chunks, tab, clip, s, nt, stream); break;
     }
 }
 
 hipError_t launch_adamw(const Chunk* chunks, int n_chunks, const RepPtrs* tab, bool grad_bf16,
-                        const AdamwScalars& s, const LaunchShape& shape, hipStream_t stream)
+                        const AdamwScalars& s, const ClipState* clip, const LaunchShape& shape,
+                        hipStream_t stream)
 {
     if (n_chunks <= 0) return hipSuccess;
     const int grid = grid_for(n_chunks, shape);
-    if (grad_bf16) adamw_dispatch_u<true>(grid, chunks, n_chunks, tab, s, shape, stream);
-    else adamw_dispatch_u<false>(grid, chunks, n_chunks, tab, s, shape, stream);
+    if (grad_bf16) adamw_dispatch_u<true>(grid, chunks, n_chunks, tab, clip, s, shape, stream);
+    else adamw_dispatch_u<false>(grid, chunks, n_chunks, tab, clip, s, shape, stream);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ gradient norm
+//
+// Global L2 norm of one replica's gradients for clipping (Table I, "clip grad 1"):
+// squares are formed and accumulated in double (the product of two floats is exact in
+// double), workgroup b folds chunks b, b + grid, b + 2 grid, ... in that order, lanes
+// are folded by a fixed shuffle tree, and a second one-workgroup kernel folds the
+// per-workgroup partial sums in a fixed order: no atomics, so the result is the same
+// in every run of the same launch shape.
+__device__ __forceinline__ double block_sum(double acc, double* lds)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_down(acc, off, 64);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) lds[wave] = acc;
+    __syncthreads();
+    double total = 0.0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 0; w < kBlock / 64; ++w) total += lds[w];
+    }
+    return total;  // valid in thread 0
+}
+
+template <bool BF16>
+__device__ __forceinline__ double sq4(typename GradVec<BF16>::type x)
+{
+    const vfloat4 f = GradVec<BF16>::widen(x);
+    double a = static_cast<double>(f.x) * static_cast<double>(f.x);
+    a += static_cast<double>(f.y) * static_cast<double>(f.y);
+    a += static_cast<double>(f.z) * static_cast<double>(f.z);
+    a += static_cast<double>(f.w) * static_cast<double>(f.w);
+    return a;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void sumsq_kernel(const Chunk* __restrict__ chunks, int n_chunks,
+                                                       const RepPtrs* __restrict__ tab,
+                                                       double* __restrict__ partials)
+{
+    typedef typename GradVec<BF16>::type gvec;
+    typedef typename std::conditional<BF16, unsigned short, float>::type gscalar;
+    __shared__ double lds[kBlock / 64];
+    const int tid = threadIdx.x;
+    double acc = 0.0;
+    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const Chunk ch = chunks[c];
+        const gscalar* __restrict__ g = static_cast<const gscalar*>(tab[ch.tensor].g) + ch.off;
+        const int len = ch.len;
+        if ((reinterpret_cast<uintptr_t>(g) & (sizeof(gvec) - 1)) == 0) {
+            const int n4 = len >> 2;
+            for (int j = tid; j < n4; j += kBlock)
+                acc += sq4<BF16>(ldo<true, gvec>(g, static_cast<unsigned>(j) * static_cast<unsigned>(sizeof(gvec))));
+            const int i = (n4 << 2) + tid;
+            if (i < len) {
+                float gi;
+                if constexpr (BF16) gi = bf16_to_f32(ld<false>(g + i)); else gi = ld<false>(g + i);
+                acc += static_cast<double>(gi) * static_cast<double>(gi);
+            }
+        } else {
+            for (int i = tid; i < len; i += kBlock) {
+                float gi;
+                if constexpr (BF16) gi = bf16_to_f32(ld<false>(g + i)); else gi = ld<false>(g + i);
+                acc += static_cast<double>(gi) * static_cast<double>(gi);
+            }
+        }
+    }
+    const double total = block_sum(acc, lds);
+    if (tid == 0) partials[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kBlock) void clip_finalize_kernel(const double* __restrict__ partials,
+                                                               int n_partials, float max_norm,
+                                                               ClipState* __restrict__ out)
+{
+    __shared__ double lds[kBlock / 64];
+    double acc = 0.0;
+    for (int i = threadIdx.x; i < n_partials; i += kBlock) acc += partials[i];
+    const double total = block_sum(acc, lds);
+    if (threadIdx.x == 0) {
+        const double norm = sqrt(total);
+        const double coef = static_cast<double>(max_norm) / (norm + 1e-6);
+        out->sumsq = total;
+        out->norm = norm;
+        out->coef = coef < 1.0 ? static_cast<float>(coef) : 1.0f;
+        out->reserved = 0.0f;
+    }
+}
+
+hipError_t launch_grad_norm(const Chunk* chunks, int n_chunks, const RepPtrs* tab, bool grad_bf16,
+                            double* partials, int n_partials, float max_norm, ClipState* out,
+                            hipStream_t stream)
+{
+    if (n_partials > n_chunks) n_partials = n_chunks;
+    if (n_partials > 0) {
+        if (grad_bf16) hipLaunchKernelGGL(sumsq_kernel<true>, dim3(n_partials), dim3(kBlock), 0, stream,
+                                          chunks, n_chunks, tab, partials);
+        else hipLaunchKernelGGL(sumsq_kernel<false>, dim3(n_partials), dim3(kBlock), 0, stream, chunks,
+                                n_chunks, tab, partials);
+    }
+    hipLaunchKernelGGL(clip_finalize_kernel, dim3(1), dim3(kBlock), 0, stream, partials,
+                       n_partials > 0 ? n_partials : 0, max_norm, out);
     return hipGetLastError();
 }
 

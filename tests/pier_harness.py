@@ -142,9 +142,23 @@ class Run:
             return np.ascontiguousarray(x.view(torch.int16).cpu().numpy().view(np.uint16))
         return np.ascontiguousarray(x.cpu().numpy())
 
-    def inner_steps(self, H, shared_stream=False):
+    def _oracle_sumsq(self, g):
+        """Sum of squares of the whole gradient of replica g's buffers, by the oracle, tensor by
+        tensor in list order (the sample cannot stand in for a reduction over every element)."""
+        ss = 0.0
+        for t in self.Gd[g].tensors:
+            if t.numel() == 0:
+                continue
+            h = t.cpu()
+            a = h.view(torch.int16).numpy().view(np.uint16) if h.dtype == torch.bfloat16 else h.numpy()
+            ss = O.sumsq(np.ascontiguousarray(a), ss)
+        return ss
+
+    def inner_steps(self, H, shared_stream=False, clip=None):
         """H AdamW steps on every replica.  shared_stream: every replica consumes the
-        same gradient draw (the synchronised lazy-start phase)."""
+        same gradient draw (the synchronised lazy-start phase).  clip: max gradient norm
+        (global-norm clipping in front of every step)."""
+        self.clip_log = []
         for _ in range(H):
             self.t += 1
             for g in range(self.G):
@@ -152,8 +166,19 @@ class Run:
                 self.Gd[g].fill_normal(seed=self.seed, stream=src, step=self.t, std=self.grad_std,
                                        hip_stream=self.stream)
                 gs = self._take(self.Gd[g].flat)           # synchronises; the oracle's copy of the bits
-                pier.pier_inner_adamw(self.ctx, g, step=self.t, stream=self.stream, **self.hp)
-                O.adamw(self.oP[g], self.oM1[g], self.oV[g], gs, step=self.t, **self.hp)
+                if clip is None:
+                    pier.pier_inner_adamw(self.ctx, g, step=self.t, stream=self.stream, **self.hp)
+                    O.adamw(self.oP[g], self.oM1[g], self.oV[g], gs, step=self.t, **self.hp)
+                else:
+                    pier.pier_inner_adamw_clipped(self.ctx, g, step=self.t, max_norm=clip, stream=self.stream,
+                                                  **self.hp)
+                    ss = self._oracle_sumsq(g)
+                    coef = O.clip_coef(ss, clip)
+                    hp = dict(self.hp)
+                    hp["grad_scale"] = hp.get("grad_scale", 1.0) * coef
+                    O.adamw(self.oP[g], self.oM1[g], self.oV[g], gs, step=self.t, **hp)
+                    norm_d, coef_d = pier.pier_grad_norm_last(self.ctx, g, stream=self.stream)
+                    self.clip_log.append((np.sqrt(ss), coef, norm_d, coef_d))
 
     def outer(self, *, mu, lr, phase):
         if self.offload:

@@ -114,6 +114,54 @@ def test_grad_scale_and_other_hyperparameters():
     r.check("grad_scale")
 
 
+# ------------------------------------------------------------------ gradient clipping
+
+def _check_clip_log(r, expect_active):
+    assert r.clip_log
+    for norm_o, coef_o, norm_d, coef_d in r.clip_log:
+        assert abs(norm_d - norm_o) <= 1e-11 * norm_o            # double sums, different fold order
+        assert abs(coef_d - coef_o) <= 6e-8 * coef_o              # equal up to the last fp32 bit
+        assert (coef_o < 1.0) == expect_active
+
+
+@pytest.mark.parametrize("pad,bf16", [(0, False), (1, False), (0, True), (1, True)])
+def test_clipped_adamw_all_elements(pad, bf16):
+    """Global-norm clipping in front of the AdamW step: norm, coefficient and the step."""
+    H_ = _harness()
+    _log("clipped adamw pad=%d bf16=%d" % (pad, bf16))
+    r = H_.Run(RAGGED + [300_000], 2, pad=pad, grad_bf16=bf16, seed=23)
+    r.inner_steps(3, clip=0.1)                     # norm ~ 0.64: clipping active
+    _check_clip_log(r, True)
+    rep = r.check("clip active")
+    r.inner_steps(2, clip=5.0)                     # threshold above the norm: coefficient 1
+    _check_clip_log(r, False)
+    r.outer(mu=0.9, lr=0.7, phase=PIER)
+    rep = r.check("clip inactive")
+    _log("clipped: %s" % rep)
+    import paper_2511_17849_amd as pier
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_inner_adamw_clipped(r.ctx, 0, step=9, max_norm=0.0, **r.hp)
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_inner_adamw_clipped(r.ctx, 0, step=9, max_norm=float("nan"), **r.hp)
+
+
+def test_clipped_norm_is_reproducible_and_tiny_config():
+    """Config 1's shapes with the paper's clip threshold 1: N(0, 1e-3) gradients over 3.9 M
+    parameters have norm ~ 1.98, so every step is clipped."""
+    H_ = _harness()
+    from pier_inputs import shapes
+    w = shapes.workloads()["tiny"]
+    logs = []
+    for _ in range(2):
+        r = H_.Run(w.numels, w.G, seed=w.seed)
+        r.inner_steps(2, clip=1.0)
+        _check_clip_log(r, True)
+        r.check("tiny clipped")
+        logs.append([(n_d, c_d) for _, _, n_d, c_d in r.clip_log])
+    assert logs[0] == logs[1]                      # bit-identical norms run to run
+    assert abs(logs[0][0][0] - 1e-3 * np.sqrt(w.N)) < 0.01
+
+
 def test_runs_are_deterministic():
     H_ = _harness()
     _log("determinism")
@@ -200,6 +248,8 @@ def test_argument_errors_are_reported_not_launched():
         pier.pier_inner_adamw(ctx, 0, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=0)
     with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
         pier.pier_inner_adamw(ctx, 0, lr=1e-3, beta1=1.0, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1)
+    with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):
+        pier.pier_grad_norm_last(ctx, 0)                                       # no clipped step yet
     with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):
         pier.pier_outer_step(ctx, outer_lr=0.7, mu=0.9, phase=PIER)           # replica 1 unbound
     pier.pier_bind_replica(ctx, 1, *P)

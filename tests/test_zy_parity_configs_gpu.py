@@ -111,6 +111,28 @@ def test_config4_gpt2_xl_resident():
 
 
 @pytest.mark.timeout(600)
+def test_config4_gpt2_xl_clipped_step():
+    """One clipped AdamW step per replica at GPT-2 XL size (norm ~ 39.5, threshold 1): the oracle
+    reduces the whole 6.2 GB gradient on the host, the update is compared on the sample."""
+    import pier_harness as H_
+    from pier_inputs import shapes
+    w = shapes.workloads()["gpt2_xl"]
+    idx = H_.sample_indices(w.numels, chunk=1024)
+    r = H_.Run(w.numels, 2, seed=w.seed, sample=idx)          # two replicas are enough here
+    r.inner_steps(1, clip=1.0)
+    for norm_o, coef_o, norm_d, coef_d in r.clip_log:
+        _log("XL clip: oracle norm %.12f coef %.9g | device norm %.12f coef %.9g" % (norm_o, coef_o, norm_d, coef_d))
+        # the oracle adds 1.56e9 squares one after the other in double: its own rounding error is
+        # of order sqrt(N) * 2^-53 = 4e-12 relative (the device's tree-shaped fold is tighter)
+        assert abs(norm_d - norm_o) <= 8 * np.sqrt(w.N) * 2.0 ** -53 * norm_o
+        assert abs(coef_d - coef_o) <= 6e-8 * coef_o and coef_o < 0.03
+    rep = r.check("XL clipped")
+    _log("XL clipped: %s" % rep)
+    del r
+    _free()
+
+
+@pytest.mark.timeout(600)
 def test_config4_gpt2_xl_in_probed_arena():
     arena = _arena()
     r, rep = _run_config("gpt2_xl", arena=arena)
