@@ -118,6 +118,23 @@ float pier_oracle_clip_coef(double sumsq, float max_norm)
 }
 
 /* ------------------------------------------------------------------------
+ * BF16 model weights beside the FP32 optimizer copy (section "Experiments": BF16
+ * in models, FP32 in optimizers): after an update the working weight is the fp32
+ * value rounded to bfloat16, round to nearest, ties to even; NaN becomes the
+ * quiet NaN 0x7FC0.
+ * ---------------------------------------------------------------------- */
+void pier_oracle_to_bf16(const float* x, uint16_t* out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        uint32_t b;
+        memcpy(&b, &x[i], sizeof b);
+        if ((b & 0x7FFFFFFFu) > 0x7F800000u) { out[i] = 0x7FC0; continue; }
+        uint32_t lsb = (b >> 16) & 1u;
+        out[i] = (uint16_t)((b + 0x7FFFu + lsb) >> 16);
+    }
+}
+
+/* ------------------------------------------------------------------------
  * Outer step (Algorithm 2, the else-branch; Algorithm 1, the t mod r = 0
  * branch).  theta[g] is group g's current model, a the model at the previous
  * synchronisation (theta_{t-r}), M the outer momentum.

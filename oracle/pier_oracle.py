@@ -60,6 +60,8 @@ class Oracle:
         L.pier_oracle_sumsq_bf16.restype = f64
         L.pier_oracle_clip_coef.argtypes = [f64, f32]
         L.pier_oracle_clip_coef.restype = f32
+        L.pier_oracle_to_bf16.argtypes = [f32p, ctypes.POINTER(ctypes.c_uint16), i64]
+        L.pier_oracle_to_bf16.restype = None
         self._L = L
 
     def adamw(self, p, m, v, g, *, lr, beta1, beta2, eps, weight_decay, step, grad_scale=1.0):
@@ -95,6 +97,12 @@ class Oracle:
     def clip_coef(self, sumsq, max_norm):
         """fp32 factor the gradients are multiplied by: min(1, max_norm / (sqrt(sumsq) + 1e-6))."""
         return self._L.pier_oracle_clip_coef(sumsq, max_norm)
+
+    def to_bf16(self, x):
+        """bfloat16 bit patterns (uint16) of the float32 array x, round to nearest even."""
+        out = np.empty(x.size, np.uint16)
+        self._L.pier_oracle_to_bf16(_f32(x), out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)), x.size)
+        return out
 
     def phase(self, t, T):
         return self._L.pier_oracle_phase(t, T)
@@ -142,6 +150,10 @@ def sumsq(g, acc=0.0):
 
 def clip_coef(sumsq_, max_norm):
     return default().clip_coef(sumsq_, max_norm)
+
+
+def to_bf16(x):
+    return default().to_bf16(x)
 
 
 def phase(t, T):

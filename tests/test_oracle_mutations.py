@@ -36,6 +36,9 @@ MUTATIONS = [
      "double pier_oracle_sumsq(const float* g, int64_t n, double acc)\n{ acc = 0;"),
     ("clip: bf16 shifted wrong", "uint32_t bits = (uint32_t)g[i] << 16;\n        float gf;\n        memcpy(&gf, &bits, sizeof gf);\n        acc",
      "uint32_t bits = (uint32_t)g[i] << 15;\n        float gf;\n        memcpy(&gf, &bits, sizeof gf);\n        acc"),
+    ("bf16: truncation instead of rounding", "out[i] = (uint16_t)((b + 0x7FFFu + lsb) >> 16);", "out[i] = (uint16_t)(b >> 16);"),
+    ("bf16: ties away from zero", "out[i] = (uint16_t)((b + 0x7FFFu + lsb) >> 16);", "out[i] = (uint16_t)((b + 0x8000u) >> 16);"),
+    ("bf16: NaN not quieted", "if ((b & 0x7FFFFFFFu) > 0x7F800000u) { out[i] = 0x7FC0; continue; }", ""),
     ("sum instead of mean", "float d = s * invG;", "float d = s;"),
     ("anchor minus model", "s = s + (theta[g][i] - a[i]);", "s = s + (a[i] - theta[g][i]);"),
     ("first group only", "for (int g = 0; g < G; ++g) s = s + (theta[g][i] - a[i]);",
@@ -68,6 +71,7 @@ def battery():
         (pins.test_adamw_matches_torch_library, (pins.HP,)),
         (pins.test_adamw_bf16_gradients_widen_exactly, ()),
         (pins.test_adamw_grad_scale_is_a_gradient_multiplier, ()),
+        (pins.test_bf16_rounding_matches_the_library_and_the_definition, ()),
         (pins.test_clip_hand_case_and_closed_form, ()),
         (pins.test_clip_matches_torch_clip_grad_norm, ()),
         (pins.test_outer_single_group_unit_rate_returns_the_model, ()),

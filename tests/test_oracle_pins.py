@@ -197,6 +197,33 @@ def test_clip_matches_torch_clip_grad_norm():
         assert np.array_equal(x, y)
 
 
+# ---------------------------------------------------------------- bf16 working weights
+
+def test_bf16_rounding_matches_the_library_and_the_definition():
+    rng = np.random.default_rng(13)
+    x = np.concatenate([
+        rng.normal(0, 0.02, 100_000).astype(np.float32),
+        np.array([0.0, -0.0, 1.0, -1.0, np.inf, -np.inf, 1e-40, -1e-40, 3.3895314e38, 65504.0], np.float32),
+        # exact ties: 1 + 2^-8 (even below -> down), 1 + 3*2^-8 (odd below -> up)
+        np.array([1.00390625, 1.01171875, -1.00390625, -1.01171875], np.float32),
+    ])
+    got = O.to_bf16(np.ascontiguousarray(x))
+    lib = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, lib)
+    # definition: nearest representable value, never further than half a bf16 ulp
+    back = (got.astype(np.uint32) << 16).view(np.float32)
+    fin = np.isfinite(x) & (np.abs(x) < 3e38) & (np.abs(x) > 1e-30)
+    assert np.all(np.abs(back[fin] - x[fin]) <= np.abs(x[fin]) * 2.0 ** -8)
+    ties = O.to_bf16(np.array([1.00390625, 1.01171875], np.float32))
+    assert list(ties) == [0x3F80, 0x3F82]                       # ties go to the even mantissa
+    assert O.to_bf16(np.array([np.nan], np.float32))[0] == 0x7FC0
+    # NaNs whose payload would carry into the exponent or sign if they were rounded like numbers
+    nans = np.array([0x7FFFFFFF, 0xFFFFFFFF, 0x7F800001, 0xFF800001], np.uint32).view(np.float32)
+    assert list(O.to_bf16(nans)) == [0x7FC0] * 4
+    lib = torch.from_numpy(nans.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert all((v & 0x7F80) == 0x7F80 and (v & 0x007F) != 0 for v in lib)      # the library keeps them NaN too
+
+
 # ---------------------------------------------------------------- outer step
 
 def test_outer_single_group_unit_rate_returns_the_model():
