@@ -87,6 +87,15 @@ pier_status pier_ctx_set_launch(pier_ctx* ctx, int64_t chunk_elems, int unroll, 
 pier_status pier_bind_replica(pier_ctx* ctx, int replica, float* const* p, float* const* m,
                               float* const* v, const void* const* grad, int grad_is_bf16);
 
+/* Optional bfloat16 working copy of replica `replica`'s parameters (section
+ * "Experiments": BF16 in models, FP32 in optimizers).  w_bf16 is a HOST array of
+ * n_tensors DEVICE pointers to 2-byte elements, or NULL to unbind.  Once bound, every
+ * step that writes theta_g (pier_inner_adamw[_clipped]; the Pier phase of the outer
+ * step, resident or offloaded) also writes bfloat16(theta_g) there, rounded to nearest
+ * even (NaN -> 0x7FC0), in the same pass (+2 B/param written).  The outer step needs
+ * the working copies of all replicas bound, or of none.  Needs the replica bound. */
+pier_status pier_bind_shadow(pier_ctx* ctx, int replica, uint16_t* const* w_bf16);
+
 typedef enum {
     PIER_LOC_DEVICE = 0,     /* anchor[i], momentum[i]: device pointer of tensor i      */
     PIER_LOC_HOST_PINNED = 1 /* anchor[0], momentum[0]: one flat PINNED host array each,

@@ -63,6 +63,7 @@ def _load():
         "pier_ctx_numel": (i64, [vp]),
         "pier_ctx_set_launch": (i32, [vp, i64, i32, i32, i32]),
         "pier_bind_replica": (i32, [vp, i32, pp, pp, pp, pp, i32]),
+        "pier_bind_shadow": (i32, [vp, i32, pp]),
         "pier_bind_outer": (i32, [vp, i32, pp, pp]),
         "pier_inner_adamw": (i32, [vp, i32, ctypes.POINTER(AdamwHP), vp]),
         "pier_inner_adamw_clipped": (i32, [vp, i32, ctypes.POINTER(AdamwHP), f32, vp]),
@@ -160,6 +161,12 @@ def pier_bind_replica(ctx, replica, p, m, v, grad, grad_is_bf16=False):
     ctx._keep[("rep", replica)] = (list(p), list(m), list(v), list(grad))
     _check(_load().pier_bind_replica(ctx.handle, int(replica), _ptr_array(p), _ptr_array(m),
                                      _ptr_array(v), _ptr_array(grad), 1 if grad_is_bf16 else 0))
+
+
+def pier_bind_shadow(ctx, replica, w_bf16):
+    """w_bf16: list of bfloat16 device tensors (one per model tensor), or None to unbind."""
+    ctx._keep[("shadow", replica)] = list(w_bf16) if w_bf16 is not None else None
+    _check(_load().pier_bind_shadow(ctx.handle, int(replica), _ptr_array(w_bf16) if w_bf16 is not None else None))
 
 
 def pier_bind_outer(ctx, loc, anchor, momentum):

@@ -74,6 +74,7 @@ struct pier_ctx {
     RepPtrs* d_rep = nullptr;
     std::vector<char> rep_bound;
     std::vector<char> rep_bf16;
+    std::vector<char> rep_shadow;
 
     double* d_partials = nullptr;  // n_replicas * kMaxNormPartials partial sums of the norm pass
     ClipState* d_clip = nullptr;   // one per replica
@@ -260,6 +261,7 @@ pier_status pier_ctx_create(pier_ctx** out, int n_tensors, const int64_t* numel,
         c->h_rep.assign(static_cast<size_t>(n_replicas) * n_tensors, RepPtrs{});
         c->rep_bound.assign(n_replicas, 0);
         c->rep_bf16.assign(n_replicas, 0);
+        c->rep_shadow.assign(n_replicas, 0);
         c->clip_valid.assign(n_replicas, 0);
         const size_t rw = outer_row_words(n_replicas);
         c->h_rows.assign(rw * n_tensors, 0);
@@ -330,7 +332,12 @@ pier_status pier_bind_replica(pier_ctx* c, int replica, float* const* p, float* 
         if ((st = check_device_range(grad[i], n, gelem, c->device, "grad", i)) != PIER_OK) return st;
     }
     RepPtrs* row = c->h_rep.data() + static_cast<size_t>(replica) * c->n_tensors;
-    for (int i = 0; i < c->n_tensors; ++i) row[i] = RepPtrs{p[i], m[i], v[i], grad[i]};
+    for (int i = 0; i < c->n_tensors; ++i) {
+        row[i].p = p[i];
+        row[i].m = m[i];
+        row[i].v = v[i];
+        row[i].g = grad[i];
+    }
     PIER_HIP(hipMemcpy(c->d_rep + static_cast<size_t>(replica) * c->n_tensors, row,
                        sizeof(RepPtrs) * c->n_tensors, hipMemcpyHostToDevice));
     const size_t rw = outer_row_words(c->n_replicas);
@@ -340,6 +347,42 @@ pier_status pier_bind_replica(pier_ctx* c, int replica, float* const* p, float* 
                        hipMemcpyHostToDevice));
     c->rep_bound[replica] = 1;
     c->rep_bf16[replica] = grad_is_bf16 ? 1 : 0;
+    return PIER_OK;
+}
+
+pier_status pier_bind_shadow(pier_ctx* c, int replica, uint16_t* const* w_bf16)
+{
+    if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
+    if (replica < 0 || replica >= c->n_replicas)
+        return fail(PIER_ERR_INVALID_ARG, "replica = %d, context has %d", replica, c->n_replicas);
+    pier_status st = ensure_device(c);
+    if (st != PIER_OK) return st;
+    if (w_bf16)
+        for (int i = 0; i < c->n_tensors; ++i)
+            if ((st = check_device_range(w_bf16[i], c->numel[i], 2, c->device, "w_bf16", i)) != PIER_OK) return st;
+    RepPtrs* row = c->h_rep.data() + static_cast<size_t>(replica) * c->n_tensors;
+    const size_t rw = outer_row_words(c->n_replicas);
+    for (int i = 0; i < c->n_tensors; ++i) {
+        row[i].w = w_bf16 ? w_bf16[i] : nullptr;
+        c->h_rows[rw * i + kOuterRowHead + c->n_replicas + replica] = reinterpret_cast<uint64_t>(row[i].w);
+    }
+    PIER_HIP(hipMemcpy(c->d_rep + static_cast<size_t>(replica) * c->n_tensors, row,
+                       sizeof(RepPtrs) * c->n_tensors, hipMemcpyHostToDevice));
+    PIER_HIP(hipMemcpy(c->d_rows, c->h_rows.data(), sizeof(uint64_t) * c->h_rows.size(),
+                       hipMemcpyHostToDevice));
+    c->rep_shadow[replica] = w_bf16 ? 1 : 0;
+    return PIER_OK;
+}
+
+// The fused outer step writes the working copies of all replicas or of none.
+static pier_status outer_shadow_mode(const pier_ctx* c, bool* shadow)
+{
+    int n = 0;
+    for (int r = 0; r < c->n_replicas; ++r) n += c->rep_shadow[r] ? 1 : 0;
+    if (n != 0 && n != c->n_replicas)
+        return fail(PIER_ERR_STATE, "bfloat16 working copies are bound for %d of %d replicas; bind all or none",
+                    n, c->n_replicas);
+    *shadow = n != 0;
     return PIER_OK;
 }
 
@@ -429,7 +472,8 @@ static pier_status inner_adamw_impl(pier_ctx* c, int replica, const pier_adamw_h
         c->clip_valid[replica] = 1;
         cs = c->d_clip + replica;
     }
-    PIER_HIP(launch_adamw(c->d_chunks, c->n_chunks, tab, c->rep_bf16[replica] != 0, s, cs, c->shape, stream));
+    PIER_HIP(launch_adamw(c->d_chunks, c->n_chunks, tab, c->rep_bf16[replica] != 0,
+                          c->rep_shadow[replica] != 0, s, cs, c->shape, stream));
     return PIER_OK;
 }
 
@@ -472,8 +516,10 @@ pier_status pier_outer_step(pier_ctx* c, const pier_outer_hp* hp, void* hip_stre
     if (!c->outer_bound || c->outer_loc != PIER_LOC_DEVICE)
         return fail(PIER_ERR_STATE, "anchor and momentum are not bound as device tensors");
     if ((st = ensure_device(c)) != PIER_OK) return st;
+    bool shadow = false;
+    if ((st = outer_shadow_mode(c, &shadow)) != PIER_OK) return st;
     PIER_HIP(launch_outer(c->d_chunks, c->n_chunks, c->d_rows, c->n_replicas, nullptr, nullptr, 0,
-                          hp->mu, hp->outer_lr, hp->phase == PIER_PHASE_PIER, c->shape,
+                          hp->mu, hp->outer_lr, hp->phase == PIER_PHASE_PIER, shadow, c->shape,
                           static_cast<hipStream_t>(hip_stream)));
     return PIER_OK;
 }
@@ -503,6 +549,8 @@ pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chu
     if (chunk_bytes < 16 || chunk_bytes % 16)
         return fail(PIER_ERR_INVALID_ARG, "chunk_bytes must be a positive multiple of 16");
     if ((st = ensure_device(c)) != PIER_OK) return st;
+    bool shadow = false;
+    if ((st = outer_shadow_mode(c, &shadow)) != PIER_OK) return st;
     if (stats) std::memset(stats, 0, sizeof *stats);
     if (c->N == 0) return PIER_OK;
 
@@ -579,7 +627,7 @@ pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chu
         PIER_HIP(hipEventRecord(EV(k, KER_B), sc));
         PIER_HIP(launch_outer(plan.d_chunks + plan.chunk_begin[k],
                               plan.chunk_begin[k + 1] - plan.chunk_begin[k], c->d_rows, c->n_replicas,
-                              sa, sM, lo, hp->mu, hp->outer_lr, hp->phase == PIER_PHASE_PIER,
+                              sa, sM, lo, hp->mu, hp->outer_lr, hp->phase == PIER_PHASE_PIER, shadow,
                               c->shape, sc));
         PIER_HIP(hipEventRecord(EV(k, KER_E), sc));
 

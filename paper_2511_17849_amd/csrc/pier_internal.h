@@ -16,22 +16,25 @@ struct Chunk {
 };
 static_assert(sizeof(Chunk) == 16, "chunk entries are read as one 16-byte load");
 
-// Per-tensor pointers of one replica.
+// Per-tensor pointers of one replica.  w: bfloat16 working copy of p (may be null).
 struct RepPtrs {
     float* p;
     float* m;
     float* v;
     const void* g;
+    unsigned short* w;
+    void* reserved;
 };
 
-// Per-tensor row of the outer step's table: 4 + G eight-byte words, contiguous so that
+// Per-tensor row of the outer step's table: 4 + 2G eight-byte words, contiguous so that
 // a workgroup fetches everything it needs about its tensor with one scalar load:
 //   word 0: anchor pointer   word 1: momentum pointer
 //   word 2: flat_start = number of elements in the tensors before this one (its
 //           position in the flat host arrays of the offload path)
 //   word 3: reserved         words 4 .. 4+G-1: theta pointers of replicas 0 .. G-1
+//   words 4+G .. 4+2G-1: bfloat16 working-copy pointers of the replicas (or null)
 constexpr int kOuterRowHead = 4;
-inline size_t outer_row_words(int G) { return static_cast<size_t>(kOuterRowHead + G); }
+inline size_t outer_row_words(int G) { return static_cast<size_t>(kOuterRowHead + 2 * G); }
 
 struct AdamwScalars {
     float lr, beta1, beta2, om1, om2, eps, wd, bc1, bc2, grad_scale;
@@ -56,9 +59,10 @@ struct ClipState {
 constexpr int kMaxNormPartials = 16384;  // workgroups (= partial sums) of the norm pass
 
 // clip: nullptr, or the replica's ClipState whose coef multiplies grad_scale.
+// shadow: also write bfloat16(theta) through RepPtrs::w.
 hipError_t launch_adamw(const Chunk* chunks, int n_chunks, const RepPtrs* tab, bool grad_bf16,
-                        const AdamwScalars& s, const ClipState* clip, const LaunchShape& shape,
-                        hipStream_t stream);
+                        bool shadow, const AdamwScalars& s, const ClipState* clip,
+                        const LaunchShape& shape, hipStream_t stream);
 
 // Sum of squares of a replica's gradients: n_partials (<= kMaxNormPartials) workgroups
 // write one double each, then one workgroup folds them and the clip coefficient into *out.
@@ -70,9 +74,10 @@ hipError_t launch_grad_norm(const Chunk* chunks, int n_chunks, const RepPtrs* ta
 // and momentum of element e of the flat index space are flat_a[e - flat_lo] and
 // flat_M[e - flat_lo] (staging slot of an offload piece) and the rows supply only
 // flat_start and the theta pointers; otherwise words 0 and 1 are used.
+// shadow (Pier phase only): also write bfloat16(theta) to every replica's working copy.
 hipError_t launch_outer(const Chunk* chunks, int n_chunks, const uint64_t* rows, int G,
                         float* flat_a, float* flat_M, int64_t flat_lo, float mu, float lr,
-                        bool pier_phase, const LaunchShape& shape, hipStream_t stream);
+                        bool pier_phase, bool shadow, const LaunchShape& shape, hipStream_t stream);
 
 // Two-stream in-place streaming pass used by the placement probe: reads n4 16-byte
 // vectors from x and y, writes them back to where they came from.

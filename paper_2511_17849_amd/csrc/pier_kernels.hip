@@ -66,6 +66,25 @@ __device__ __forceinline__ float bf16_to_f32(unsigned short h)
     return __uint_as_float(static_cast<unsigned int>(h) << 16);
 }
 
+// fp32 -> bfloat16, round to nearest even; NaN becomes the quiet NaN 0x7FC0.  This is
+// the working weight the model computes with (BF16 in models, FP32 in optimizers).
+__device__ __forceinline__ unsigned short f32_to_bf16(float f)
+{
+    const unsigned int b = __float_as_uint(f);
+    const unsigned int r = (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+    return static_cast<unsigned short>((b & 0x7FFFFFFFu) > 0x7F800000u ? 0x7FC0u : r);
+}
+
+__device__ __forceinline__ vushort4 f32_to_bf16(vfloat4 f)
+{
+    vushort4 r;
+    r.x = f32_to_bf16(f.x);
+    r.y = f32_to_bf16(f.y);
+    r.z = f32_to_bf16(f.z);
+    r.w = f32_to_bf16(f.w);
+    return r;
+}
+
 // ------------------------------------------------------------------ inner AdamW
 //
 // AdamW with decoupled weight decay and bias correction (the inner optimizer of
@@ -119,9 +138,9 @@ __device__ __forceinline__ void adamw_vec(vfloat4& P, vfloat4& M, vfloat4& V, co
     }
 }
 
-template <bool BF16, typename GS>
+template <bool BF16, bool SHADOW, typename GS>
 __device__ __forceinline__ void adamw_scalar(float* p, float* m, float* v, const GS* g,
-                                             const AdamwScalars& s)
+                                             unsigned short* w, const AdamwScalars& s)
 {
     float pi = ld<false>(p), mi = ld<false>(m), vi = ld<false>(v), gi;
     if constexpr (BF16) gi = bf16_to_f32(ld<false>(g)); else gi = ld<false>(g);
@@ -129,9 +148,10 @@ __device__ __forceinline__ void adamw_scalar(float* p, float* m, float* v, const
     st<false>(p, pi);
     st<false>(m, mi);
     st<false>(v, vi);
+    if constexpr (SHADOW) st<false>(w, f32_to_bf16(pi));
 }
 
-template <int UNROLL, bool BF16, bool NT>
+template <int UNROLL, bool BF16, bool NT, bool SHADOW>
 __global__ __launch_bounds__(kBlock) void adamw_kernel(const Chunk* __restrict__ chunks,
                                                        int n_chunks,
                                                        const RepPtrs* __restrict__ tab,
@@ -152,11 +172,13 @@ __global__ __launch_bounds__(kBlock) void adamw_kernel(const Chunk* __restrict__
         float* __restrict__ m = t.m + ch.off;
         float* __restrict__ v = t.v + ch.off;
         const gscalar* __restrict__ g = static_cast<const gscalar*>(t.g) + ch.off;
+        unsigned short* __restrict__ w = SHADOW ? t.w + ch.off : nullptr;
         const int len = ch.len;
 
         const uintptr_t mis = (reinterpret_cast<uintptr_t>(p) | reinterpret_cast<uintptr_t>(m) |
                                reinterpret_cast<uintptr_t>(v)) & 15u;
-        const uintptr_t gmis = reinterpret_cast<uintptr_t>(g) & (sizeof(gvec) - 1);
+        const uintptr_t gmis = (reinterpret_cast<uintptr_t>(g) & (sizeof(gvec) - 1)) |
+                               (reinterpret_cast<uintptr_t>(w) & 7u);
         if ((mis | gmis) == 0) {
             constexpr unsigned kG = sizeof(gvec);
             const int n4 = len >> 2;
@@ -179,6 +201,7 @@ __global__ __launch_bounds__(kBlock) void adamw_kernel(const Chunk* __restrict__
                     sto<NT>(p, i * 16u, P[u]);
                     sto<NT>(m, i * 16u, M[u]);
                     sto<NT>(v, i * 16u, V[u]);
+                    if constexpr (SHADOW) sto<NT>(w, i * 8u, f32_to_bf16(P[u]));
                 }
             }
             // ragged last tile of the chunk
@@ -191,12 +214,14 @@ __global__ __launch_bounds__(kBlock) void adamw_kernel(const Chunk* __restrict__
                 sto<NT>(p, i * 16u, P);
                 sto<NT>(m, i * 16u, M);
                 sto<NT>(v, i * 16u, V);
+                if constexpr (SHADOW) sto<NT>(w, i * 8u, f32_to_bf16(P));
             }
             // up to three elements past the last whole vector
             const int i = (n4 << 2) + tid;
-            if (i < len) adamw_scalar<BF16>(p + i, m + i, v + i, g + i, s);
+            if (i < len) adamw_scalar<BF16, SHADOW>(p + i, m + i, v + i, g + i, w + i, s);
         } else {
-            for (int i = tid; i < len; i += kBlock) adamw_scalar<BF16>(p + i, m + i, v + i, g + i, s);
+            for (int i = tid; i < len; i += kBlock)
+                adamw_scalar<BF16, SHADOW>(p + i, m + i, v + i, g + i, w + i, s);
         }
     }
 }
@@ -207,37 +232,42 @@ static int grid_for(int n_chunks, const LaunchShape& shape)
     return n_chunks;
 }
 
-template <int U, bool BF16>
+template <int U, bool BF16, bool SHADOW>
 static void adamw_dispatch_nt(int grid, const Chunk* chunks, int n_chunks, const RepPtrs* tab,
                               const ClipState* clip, const AdamwScalars& s, bool nt, hipStream_t stream)
 {
-    if (nt) hipLaunchKernelGGL((adamw_kernel<U, BF16, true>), dim3(grid), dim3(kBlock), 0, stream,
+    if (nt) hipLaunchKernelGGL((adamw_kernel<U, BF16, true, SHADOW>), dim3(grid), dim3(kBlock), 0, stream,
                                chunks, n_chunks, tab, clip, s);
-    else hipLaunchKernelGGL((adamw_kernel<U, BF16, false>), dim3(grid), dim3(kBlock), 0, stream,
+    else hipLaunchKernelGGL((adamw_kernel<U, BF16, false, SHADOW>), dim3(grid), dim3(kBlock), 0, stream,
                             chunks, n_chunks, tab, clip, s);
 }
 
-template <bool BF16>
+template <bool BF16, bool SHADOW>
 static void adamw_dispatch_u(int grid, const Chunk* chunks, int n_chunks, const RepPtrs* tab,
                              const ClipState* clip, const AdamwScalars& s, const LaunchShape& shape,
                              hipStream_t stream)
 {
     const bool nt = shape.nontemporal != 0;
     switch (shape.unroll) {
-    case 1: adamw_dispatch_nt<1, BF16>(grid, chunks, n_chunks, tab, clip, s, nt, stream); break;
-    case 2: adamw_dispatch_nt<2, BF16>(grid, chunks, n_chunks, tab, clip, s, nt, stream); break;
-    default: adamw_dispatch_nt<4, BF16>(grid, chunks, n_chunks, tab, clip, s, nt, stream); break;
+    case 1: adamw_dispatch_nt<1, BF16, SHADOW>(grid, chunks, n_chunks, tab, clip, s, nt, stream); break;
+    case 2: adamw_dispatch_nt<2, BF16, SHADOW>(grid, chunks, n_chunks, tab, clip, s, nt, stream); break;
+    default: adamw_dispatch_nt<4, BF16, SHADOW>(grid, chunks, n_chunks, tab, clip, s, nt, stream); break;
     }
 }
 
 hipError_t launch_adamw(const Chunk* chunks, int n_chunks, const RepPtrs* tab, bool grad_bf16,
-                        const AdamwScalars& s, const ClipState* clip, const LaunchShape& shape,
-                        hipStream_t stream)
+                        bool shadow, const AdamwScalars& s, const ClipState* clip,
+                        const LaunchShape& shape, hipStream_t stream)
 {
     if (n_chunks <= 0) return hipSuccess;
     const int grid = grid_for(n_chunks, shape);
-    if (grad_bf16) adamw_dispatch_u<true>(grid, chunks, n_chunks, tab, clip, s, shape, stream);
-    else adamw_dispatch_u<false>(grid, chunks, n_chunks, tab, clip, s, shape, stream);
+    if (grad_bf16) {
+        if (shadow) adamw_dispatch_u<true, true>(grid, chunks, n_chunks, tab, clip, s, shape, stream);
+        else adamw_dispatch_u<true, false>(grid, chunks, n_chunks, tab, clip, s, shape, stream);
+    } else {
+        if (shadow) adamw_dispatch_u<false, true>(grid, chunks, n_chunks, tab, clip, s, shape, stream);
+        else adamw_dispatch_u<false, false>(grid, chunks, n_chunks, tab, clip, s, shape, stream);
+    }
     return hipGetLastError();
 }
 
@@ -397,9 +427,9 @@ __device__ __forceinline__ void outer_vec(vfloat4 (&TH)[G], vfloat4& A, vfloat4&
     }
 }
 
-template <int G, bool PIER>
-__device__ __forceinline__ void outer_scalar(float* const (&th)[G], float* a, float* M, int i,
-                                             float mu, float lr, float invG)
+template <int G, bool PIER, bool SHADOW>
+__device__ __forceinline__ void outer_scalar(float* const (&th)[G], unsigned short* const (&wb)[G],
+                                             float* a, float* M, int i, float mu, float lr, float invG)
 {
     float t[G];
 #pragma unroll
@@ -411,6 +441,11 @@ __device__ __forceinline__ void outer_scalar(float* const (&th)[G], float* a, fl
     if constexpr (PIER) {
 #pragma unroll
         for (int g = 0; g < G; ++g) st<false>(th[g] + i, t[g]);
+        if constexpr (SHADOW) {
+            const unsigned short h = f32_to_bf16(av);       // theta_g == new anchor for every g
+#pragma unroll
+            for (int g = 0; g < G; ++g) st<false>(wb[g] + i, h);
+        }
     }
 }
 
@@ -420,6 +455,7 @@ struct OuterArgs {
     int64_t flat_lo;
     int n_chunks;
     int G;
+    int shadow;
     float mu, lr, invG;
 };
 
@@ -431,16 +467,18 @@ struct OuterRow {
     int64_t flat_start;
     int64_t reserved;
     float* th[G];
+    unsigned short* wb[G];
 };
 
 // The tables are separate const __restrict__ parameters: only then may the compiler
 // read them through the scalar unit (they are never written by a kernel).
-template <int G, int UNROLL, bool FLAT, bool PIER, bool NT>
+template <int G, int UNROLL, bool FLAT, bool PIER, bool NT, bool SHADOW>
 __global__ __launch_bounds__(kBlock) void outer_kernel(const Chunk* __restrict__ chunks,
                                                        const OuterRow<G>* __restrict__ rows,
                                                        OuterArgs A)
 {
-    static_assert(sizeof(OuterRow<G>) == (kOuterRowHead + G) * 8, "row layout");
+    static_assert(sizeof(OuterRow<G>) == (kOuterRowHead + 2 * G) * 8, "row layout");
+    static_assert(PIER || !SHADOW, "the lazy-start phase does not touch the replicas");
     const int tid = threadIdx.x;
     constexpr int kTile = kBlock * UNROLL;
 
@@ -458,15 +496,19 @@ __global__ __launch_bounds__(kBlock) void outer_kernel(const Chunk* __restrict__
             M = row.M + ch.off;
         }
         float* th[G];
+        unsigned short* wb[G];
         uintptr_t mis = reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(M);
+        uintptr_t wmis = 0;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             th[g] = row.th[g] + ch.off;
             mis |= reinterpret_cast<uintptr_t>(th[g]);
+            wb[g] = SHADOW ? row.wb[g] + ch.off : nullptr;
+            wmis |= reinterpret_cast<uintptr_t>(wb[g]);
         }
         const int len = ch.len;
 
-        if ((mis & 15u) == 0) {
+        if (((mis & 15u) | (wmis & 7u)) == 0) {
             const int n4 = len >> 2;
             int base = 0;
             for (; base + kTile <= n4; base += kTile) {
@@ -489,6 +531,11 @@ __global__ __launch_bounds__(kBlock) void outer_kernel(const Chunk* __restrict__
 #pragma unroll
                         for (int g = 0; g < G; ++g) sto<NT>(th[g], o, TH[u][g]);
                     }
+                    if constexpr (SHADOW) {
+                        const vushort4 h = f32_to_bf16(Av[u]);
+#pragma unroll
+                        for (int g = 0; g < G; ++g) sto<NT>(wb[g], o >> 1, h);
+                    }
                 }
             }
             for (int j = base + tid; j < n4; j += kBlock) {
@@ -503,11 +550,17 @@ __global__ __launch_bounds__(kBlock) void outer_kernel(const Chunk* __restrict__
 #pragma unroll
                     for (int g = 0; g < G; ++g) sto<NT>(th[g], o, TH[g]);
                 }
+                if constexpr (SHADOW) {
+                    const vushort4 h = f32_to_bf16(Av);
+#pragma unroll
+                    for (int g = 0; g < G; ++g) sto<NT>(wb[g], o >> 1, h);
+                }
             }
             const int i = (n4 << 2) + tid;
-            if (i < len) outer_scalar<G, PIER>(th, a, M, i, A.mu, A.lr, A.invG);
+            if (i < len) outer_scalar<G, PIER, SHADOW>(th, wb, a, M, i, A.mu, A.lr, A.invG);
         } else {
-            for (int i = tid; i < len; i += kBlock) outer_scalar<G, PIER>(th, a, M, i, A.mu, A.lr, A.invG);
+            for (int i = tid; i < len; i += kBlock)
+                outer_scalar<G, PIER, SHADOW>(th, wb, a, M, i, A.mu, A.lr, A.invG);
         }
     }
 }
@@ -524,7 +577,7 @@ __global__ __launch_bounds__(kBlock) void outer_kernel_anyG(const Chunk* __restr
     const int tid = threadIdx.x;
     for (int c = blockIdx.x; c < A.n_chunks; c += gridDim.x) {
         const Chunk ch = chunks[c];
-        const uint64_t* __restrict__ row = rows + static_cast<int64_t>(ch.tensor) * (kOuterRowHead + A.G);
+        const uint64_t* __restrict__ row = rows + static_cast<int64_t>(ch.tensor) * (kOuterRowHead + 2 * A.G);
         float* __restrict__ a;
         float* __restrict__ M;
         if constexpr (FLAT) {
@@ -551,6 +604,11 @@ __global__ __launch_bounds__(kBlock) void outer_kernel_anyG(const Chunk* __restr
                 st<false>(a + i, x);
                 for (int g = 0; g < A.G; ++g)
                     st<false>(reinterpret_cast<float*>(row[kOuterRowHead + g]) + ch.off + i, x);
+                if (A.shadow) {
+                    const unsigned short h = f32_to_bf16(x);
+                    for (int g = 0; g < A.G; ++g)
+                        st<false>(reinterpret_cast<unsigned short*>(row[kOuterRowHead + A.G + g]) + ch.off + i, h);
+                }
             } else {
                 st<false>(a + i, s2 * A.invG);
             }
@@ -563,12 +621,21 @@ struct OuterTables {
     const uint64_t* rows;
 };
 
+template <int G, int U, bool FLAT, bool PIER, bool SHADOW>
+static void outer_launch(int grid, const OuterTables& T, const OuterArgs& A, bool nt, hipStream_t stream)
+{
+    const OuterRow<G>* ROWS = reinterpret_cast<const OuterRow<G>*>(T.rows);
+    if (nt) hipLaunchKernelGGL((outer_kernel<G, U, FLAT, PIER, true, SHADOW>), dim3(grid), dim3(kBlock), 0, stream, T.chunks, ROWS, A);
+    else hipLaunchKernelGGL((outer_kernel<G, U, FLAT, PIER, false, SHADOW>), dim3(grid), dim3(kBlock), 0, stream, T.chunks, ROWS, A);
+}
+
 template <int G, int U, bool FLAT, bool PIER>
 static void outer_dispatch_nt(int grid, const OuterTables& T, const OuterArgs& A, bool nt, hipStream_t stream)
 {
-    const OuterRow<G>* ROWS = reinterpret_cast<const OuterRow<G>*>(T.rows);
-    if (nt) hipLaunchKernelGGL((outer_kernel<G, U, FLAT, PIER, true>), dim3(grid), dim3(kBlock), 0, stream, T.chunks, ROWS, A);
-    else hipLaunchKernelGGL((outer_kernel<G, U, FLAT, PIER, false>), dim3(grid), dim3(kBlock), 0, stream, T.chunks, ROWS, A);
+    if constexpr (PIER) {
+        if (A.shadow) { outer_launch<G, U, FLAT, true, true>(grid, T, A, nt, stream); return; }
+    }
+    outer_launch<G, U, FLAT, PIER, false>(grid, T, A, nt, stream);
 }
 
 template <int G, bool FLAT, bool PIER>
@@ -604,7 +671,7 @@ static void outer_dispatch_g(int grid, const OuterTables& T, const OuterArgs& A,
 
 hipError_t launch_outer(const Chunk* chunks, int n_chunks, const uint64_t* rows, int G,
                         float* flat_a, float* flat_M, int64_t flat_lo, float mu, float lr,
-                        bool pier_phase, const LaunchShape& shape, hipStream_t stream)
+                        bool pier_phase, bool shadow, const LaunchShape& shape, hipStream_t stream)
 {
     if (n_chunks <= 0) return hipSuccess;
     const OuterTables T{chunks, rows};
@@ -614,6 +681,7 @@ hipError_t launch_outer(const Chunk* chunks, int n_chunks, const uint64_t* rows,
     A.flat_lo = flat_lo;
     A.n_chunks = n_chunks;
     A.G = G;
+    A.shadow = (shadow && pier_phase) ? 1 : 0;
     A.mu = mu;
     A.lr = lr;
     A.invG = 1.0f / static_cast<float>(G);

@@ -68,7 +68,7 @@ class Run:
 
     def __init__(self, numels, G, *, grad_bf16=False, hp=None, seed=0, param_std=0.02, grad_std=1e-3,
                  pad=0, launch=None, offload=False, chunk_bytes=None, sample=None, shared_grad=False,
-                 stream=None, arena=None):
+                 stream=None, arena=None, shadow=False):
         self.numels, self.G, self.pad = list(numels), G, pad
         self.grad_bf16 = grad_bf16
         self.hp = hp or dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
@@ -112,6 +112,11 @@ class Run:
         for g in range(G):
             pier.pier_bind_replica(self.ctx, g, self.P[g].tensors, self.M1[g].tensors, self.V[g].tensors,
                                    self.Gd[g].tensors, grad_bf16)
+        self.W = None
+        if shadow:      # bfloat16 working copies of every replica's parameters
+            self.W = [dev.FlatList(numels, dtype=torch.bfloat16, pad=pad) for _ in range(G)]
+            for g in range(G):
+                pier.pier_bind_shadow(self.ctx, g, self.W[g].tensors)
         if offload:
             pier.pier_bind_outer(self.ctx, pier.PIER_LOC_HOST_PINNED, self.A.flat, self.Mo.flat)
             wb = pier.pier_offload_workspace_bytes(self.ctx, chunk_bytes)
@@ -132,6 +137,7 @@ class Run:
         self.oV = [np.zeros(self.idx.size, np.float32) for _ in range(G)]
         self.oA = self._take(self.A.flat)
         self.oMo = np.zeros(self.idx.size, np.float32)
+        self.oW = [np.zeros(self.idx.size, np.uint16) for _ in range(G)] if shadow else None
 
     def _take(self, flat):
         if flat.is_cuda:
@@ -179,6 +185,8 @@ class Run:
                     O.adamw(self.oP[g], self.oM1[g], self.oV[g], gs, step=self.t, **hp)
                     norm_d, coef_d = pier.pier_grad_norm_last(self.ctx, g, stream=self.stream)
                     self.clip_log.append((np.sqrt(ss), coef, norm_d, coef_d))
+                if self.oW is not None:
+                    self.oW[g] = O.to_bf16(self.oP[g])
 
     def outer(self, *, mu, lr, phase):
         if self.offload:
@@ -189,6 +197,8 @@ class Run:
         else:
             pier.pier_outer_step(self.ctx, outer_lr=lr, mu=mu, phase=phase, stream=self.stream)
         O.outer(self.oP, self.oA, self.oMo, mu=mu, lr=lr, phase=phase)
+        if self.oW is not None and phase == O.PIER:
+            self.oW = [O.to_bf16(p) for p in self.oP]
 
     def device_state(self):
         torch.cuda.synchronize()
@@ -197,12 +207,16 @@ class Run:
             d["P%d" % g] = self._take(self.P[g].flat)
             d["M1_%d" % g] = self._take(self.M1[g].flat)
             d["V%d" % g] = self._take(self.V[g].flat)
+            if self.W is not None:
+                d["W%d" % g] = self._take(self.W[g].flat)
         return d
 
     def oracle_state(self):
         d = {"A": self.oA, "Mo": self.oMo}
         for g in range(self.G):
             d["P%d" % g], d["M1_%d" % g], d["V%d" % g] = self.oP[g], self.oM1[g], self.oV[g]
+            if self.oW is not None:
+                d["W%d" % g] = self.oW[g]
         return d
 
     def check(self, label=""):
@@ -212,6 +226,9 @@ class Run:
         for k in ref:
             g_, r_ = got[k], ref[k]
             assert g_.shape == r_.shape
+            if k[0] == "W":      # bfloat16 bit patterns: an integer result, compared exactly
+                assert np.array_equal(g_, r_), "%s %s: %d bf16 codes differ" % (label, k, (g_ != r_).sum())
+                continue
             assert np.all(np.isfinite(g_)), (label, k)
             ok = tol_ok(g_, r_)
             assert ok.all(), "%s %s: %d of %d beyond 1e-6*max(1,|x|), worst %.3e" % (

@@ -114,6 +114,53 @@ def test_grad_scale_and_other_hyperparameters():
     r.check("grad_scale")
 
 
+# ------------------------------------------------------------------ bf16 working weights
+
+@pytest.mark.parametrize("G,pad", [(1, 0), (2, 1), (3, 0), (8, 0)])
+def test_bf16_working_copies(G, pad):
+    """The bfloat16 copy of theta written by the AdamW step and by the Pier outer step
+    (not by the lazy-start step), bit for bit; odd sizes and 2-byte aligned tensors too."""
+    H_ = _harness()
+    _log("bf16 working copies G=%d pad=%d" % (G, pad))
+    r = H_.Run(RAGGED + [150_000], G, pad=pad, seed=29, shadow=True)
+    r.inner_steps(2, shared_stream=True)
+    r.outer(mu=0.9, lr=0.0, phase=WARMUP)
+    r.check("shadow warmup")                       # working copies still those of the last inner step
+    r.inner_steps(2, clip=0.05)
+    r.outer(mu=0.95, lr=0.8, phase=PIER)
+    rep = r.check("shadow pier")
+    st = r.device_state()
+    for g in range(1, G):
+        assert np.array_equal(st["W0"], st["W%d" % g])
+    assert np.abs((st["W0"].astype(np.uint32) << 16).view(np.float32) - st["P0"]).max() <= 2.0 ** -8 * np.abs(st["P0"]).max()
+    _log("bf16 working copies: %s" % rep)
+
+
+def test_bf16_working_copies_offload_and_partial_binding():
+    import paper_2511_17849_amd as pier
+    H_ = _harness()
+    numels = [70_000, 1024, 4, 0, 300_000]
+    res = H_.Run(numels, 2, seed=31, shadow=True)
+    off = H_.Run(numels, 2, seed=31, shadow=True, offload=True, chunk_bytes=262144)
+    for r in (res, off):
+        r.inner_steps(2)
+        r.outer(mu=0.9, lr=1.1, phase=PIER)
+    off.check("shadow offload")
+    a, b = res.device_state(), off.device_state()
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    pier.pier_bind_shadow(res.ctx, 1, None)        # one replica without a working copy
+    with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):
+        pier.pier_outer_step(res.ctx, outer_lr=0.7, mu=0.9, phase=PIER)
+    pier.pier_bind_shadow(res.ctx, 0, None)        # none: plain path again
+    before = res.device_state()
+    old_w, res.W, res.oW = res.W, None, None
+    res.inner_steps(1)
+    res.outer(mu=0.9, lr=0.7, phase=PIER)
+    res.check("shadow unbound")
+    assert np.array_equal(before["W0"], res._take(old_w[0].flat))      # no longer written
+
+
 # ------------------------------------------------------------------ gradient clipping
 
 def _check_clip_log(r, expect_active):
