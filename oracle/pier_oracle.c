@@ -206,6 +206,22 @@ float pier_oracle_outer_lr(int64_t t, int64_t T)
     return 0.9f;
 }
 
+/* Inner learning rate (Table I: cosine decay style, learning rate warmup proportion 2%,
+ * a minimum learning rate, decay iterations = training iterations): linear from 0 to
+ * lr_max over the first warmup_frac * T iterations (iteration t uses lr_max * t / W,
+ * W = warmup_frac * T), then half a cosine from lr_max at t = W down to lr_min at
+ * t = T.  Evaluated in double, rounded once to fp32. */
+float pier_oracle_inner_lr(int64_t t, int64_t T, float lr_max, float lr_min, double warmup_frac)
+{
+    const double pi = 3.14159265358979323846;
+    double W = warmup_frac * (double)T;
+    if (W > 0.0 && (double)t <= W) return (float)((double)lr_max * (double)t / W);
+    if (t >= T) return lr_min;
+    double ratio = ((double)t - W) / ((double)T - W);
+    double coeff = 0.5 * (cos(pi * ratio) + 1.0);
+    return (float)((double)lr_min + coeff * ((double)lr_max - (double)lr_min));
+}
+
 /* The momentum coefficient and rate one synchronisation at iteration t uses:
  * in the lazy-start phase mu is Algorithm 1's default 0.9 and no rate applies. */
 void pier_oracle_outer_scalars(int64_t t, int64_t T, int* phase, float* mu, float* lr)

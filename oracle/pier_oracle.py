@@ -60,6 +60,8 @@ class Oracle:
         L.pier_oracle_sumsq_bf16.restype = f64
         L.pier_oracle_clip_coef.argtypes = [f64, f32]
         L.pier_oracle_clip_coef.restype = f32
+        L.pier_oracle_inner_lr.argtypes = [i64, i64, f32, f32, f64]
+        L.pier_oracle_inner_lr.restype = f32
         L.pier_oracle_to_bf16.argtypes = [f32p, ctypes.POINTER(ctypes.c_uint16), i64]
         L.pier_oracle_to_bf16.restype = None
         self._L = L
@@ -112,6 +114,9 @@ class Oracle:
 
     def outer_lr(self, t, T):
         return self._L.pier_oracle_outer_lr(t, T)
+
+    def inner_lr(self, t, T, lr_max, lr_min, warmup_frac=0.02):
+        return self._L.pier_oracle_inner_lr(t, T, lr_max, lr_min, warmup_frac)
 
     def outer_scalars(self, t, T):
         """(phase, mu, lr) that the synchronisation at iteration t of T uses."""
@@ -170,3 +175,7 @@ def outer_lr(t, T):
 
 def outer_scalars(t, T):
     return default().outer_scalars(t, T)
+
+
+def inner_lr(t, T, lr_max, lr_min, warmup_frac=0.02):
+    return default().inner_lr(t, T, lr_max, lr_min, warmup_frac)

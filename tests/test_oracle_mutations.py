@@ -39,6 +39,10 @@ MUTATIONS = [
     ("bf16: truncation instead of rounding", "out[i] = (uint16_t)((b + 0x7FFFu + lsb) >> 16);", "out[i] = (uint16_t)(b >> 16);"),
     ("bf16: ties away from zero", "out[i] = (uint16_t)((b + 0x7FFFu + lsb) >> 16);", "out[i] = (uint16_t)((b + 0x8000u) >> 16);"),
     ("bf16: NaN not quieted", "if ((b & 0x7FFFFFFFu) > 0x7F800000u) { out[i] = 0x7FC0; continue; }", ""),
+    ("inner lr: cosine over T instead of T - W", "double ratio = ((double)t - W) / ((double)T - W);", "double ratio = ((double)t - W) / ((double)T);"),
+    ("inner lr: warmup from lr_min", "return (float)((double)lr_max * (double)t / W);", "return (float)((double)lr_min + ((double)lr_max - lr_min) * (double)t / W);"),
+    ("inner lr: full cosine period", "cos(pi * ratio)", "cos(2.0 * pi * ratio)"),
+    ("inner lr: decays to zero", "(float)((double)lr_min + coeff * ((double)lr_max - (double)lr_min))", "(float)(coeff * (double)lr_max)"),
     ("sum instead of mean", "float d = s * invG;", "float d = s;"),
     ("anchor minus model", "s = s + (theta[g][i] - a[i]);", "s = s + (a[i] - theta[g][i]);"),
     ("first group only", "for (int g = 0; g < G; ++g) s = s + (theta[g][i] - a[i]);",
@@ -72,6 +76,7 @@ def battery():
         (pins.test_adamw_bf16_gradients_widen_exactly, ()),
         (pins.test_adamw_grad_scale_is_a_gradient_multiplier, ()),
         (pins.test_bf16_rounding_matches_the_library_and_the_definition, ()),
+        (pins.test_inner_lr_schedule_endpoints_and_library_cosine, ()),
         (pins.test_clip_hand_case_and_closed_form, ()),
         (pins.test_clip_matches_torch_clip_grad_norm, ()),
         (pins.test_outer_single_group_unit_rate_returns_the_model, ()),

@@ -407,6 +407,33 @@ def test_schedules_match_the_printed_constants(row):
         assert mu2 == np.float32(mu) and abs(lr2 - lr) <= 1e-7
 
 
+def test_inner_lr_schedule_endpoints_and_library_cosine():
+    # Table I: GPT-2 small 4e-4 -> 4e-5, medium 3e-4 -> 3e-5, XL 1.5e-4 -> 1.5e-5; T = 100000; 2% warmup
+    T = 100_000
+    for lr_max, lr_min in ((4e-4, 4e-5), (3e-4, 3e-5), (1.5e-4, 1.5e-5)):
+        assert O.inner_lr(2000, T, lr_max, lr_min) == np.float32(lr_max)         # end of warmup
+        assert O.inner_lr(1000, T, lr_max, lr_min) == np.float32(np.float32(lr_max) / 2.0)
+        assert O.inner_lr(T, T, lr_max, lr_min) == np.float32(lr_min)
+        assert O.inner_lr(T + 5, T, lr_max, lr_min) == np.float32(lr_min)
+        mid = O.inner_lr(51_000, T, lr_max, lr_min)                              # half way down the cosine
+        assert abs(mid - (np.float32(lr_max) + np.float32(lr_min)) / 2) < 1e-10
+        lrs = [O.inner_lr(t, T, lr_max, lr_min) for t in range(1, T + 1, 97)]
+        k = lrs.index(max(lrs))
+        assert all(a <= b for a, b in zip(lrs[:k], lrs[1:k + 1])) and all(a >= b for a, b in zip(lrs[k:], lrs[k + 1:]))
+    # the cosine leg against torch's CosineAnnealingLR (library routine), T_max = T - W steps
+    W, lr_max, lr_min = 2000, 3e-4, 3e-5
+    p = torch.nn.Parameter(torch.zeros(1))
+    opt = torch.optim.SGD([p], lr=lr_max)
+    sched = torch.optim.lr_scheduler.CosineAnnealingLR(opt, T_max=T - W, eta_min=lr_min)
+    for k in range(1, 3001):
+        opt.step()
+        sched.step()
+        if k % 500 == 0:
+            assert abs(sched.get_last_lr()[0] - O.inner_lr(W + k, T, lr_max, lr_min)) < 3e-11
+    # no warmup at all
+    assert O.inner_lr(1, 100, 1.0, 0.1, 0.0) < 1.0 and O.inner_lr(1, 100, 1.0, 0.1, 0.0) > 0.99
+
+
 def test_schedule_is_monotone_where_the_paper_says_so():
     T = 1000
     mus = [O.mu(t, T) for t in range(100, T + 1)]
