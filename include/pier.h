@@ -211,6 +211,40 @@ float pier_outer_lr_schedule(int64_t t, int64_t T);
  * default mu = 0.9; afterwards PIER with the two schedules above. */
 pier_status pier_outer_schedule(int64_t t, int64_t T, pier_outer_hp* out);
 
+/* Inner learning rate (Table I: cosine decay, 2 % warmup, minimum learning rate, decay
+ * iterations = T): lr_max * t / W for t <= W = warmup_frac * T, then half a cosine from
+ * lr_max at W to lr_min at T (lr_min beyond).  Evaluated in double, rounded to fp32. */
+float pier_inner_lr_schedule(int64_t t, int64_t T, float lr_max, float lr_min, double warmup_frac);
+
+/* -------------------------------------------------------- one training iteration
+ * Algorithm 2's loop body for iteration t (1-based) as one call, for a caller that has
+ * just put the gradients of every replica in the bound gradient tensors: the inner
+ * AdamW step of every replica with the scheduled learning rate (preceded by global-norm
+ * clipping when clip_norm > 0), and, when t is a multiple of r, the outer step with the
+ * scalars of pier_outer_schedule (mode PIER) or with DiLoCo's fixed outer learning rate
+ * 0.7 and momentum 0.9 and no lazy-start phase (mode DILOCO: the baseline the paper
+ * compares with).  The outer step runs resident or, when anchor and M are bound as
+ * pinned host arrays, through pier_offload_stream with the workspace and side streams
+ * given here.  (The paper's listing prints the inner step only for t mod r != 0; as in
+ * Algorithm 1 the step is taken every iteration.)  Everything is enqueued on
+ * `hip_stream` (plus the side streams); nothing synchronises. */
+typedef enum { PIER_MODE_PIER = 0, PIER_MODE_DILOCO = 1 } pier_mode;
+typedef struct {
+    int64_t T;                 /* training iterations                                  */
+    int64_t r;                 /* synchronisation interval                             */
+    pier_mode mode;
+    float lr_max, lr_min;      /* inner learning-rate schedule                         */
+    double warmup_frac;        /* 0.02 in Table I                                      */
+    float beta1, beta2, eps, weight_decay;
+    float clip_norm;           /* > 0: clipping threshold (Table I: 1); 0: no clipping */
+    size_t chunk_bytes;        /* offload only                                         */
+    void* workspace;           /* offload only: device staging memory                  */
+    size_t workspace_bytes;
+    void* h2d_stream;          /* offload only                                         */
+    void* d2h_stream;
+} pier_train_cfg;
+pier_status pier_train_step(pier_ctx* ctx, const pier_train_cfg* cfg, int64_t t, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -10,6 +10,7 @@ _LIB_PATH = os.path.join(_HERE, "libpier.so")
 
 PIER_PHASE_WARMUP, PIER_PHASE_PIER = 0, 1
 PIER_LOC_DEVICE, PIER_LOC_HOST_PINNED = 0, 1
+PIER_MODE_PIER, PIER_MODE_DILOCO = 0, 1
 
 
 class PierError(RuntimeError):
@@ -26,6 +27,16 @@ class AdamwHP(ctypes.Structure):
 
 class OuterHP(ctypes.Structure):
     _fields_ = [("outer_lr", ctypes.c_float), ("mu", ctypes.c_float), ("phase", ctypes.c_int)]
+
+
+class TrainCfg(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int64), ("r", ctypes.c_int64), ("mode", ctypes.c_int),
+                ("lr_max", ctypes.c_float), ("lr_min", ctypes.c_float), ("warmup_frac", ctypes.c_double),
+                ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("weight_decay", ctypes.c_float), ("clip_norm", ctypes.c_float),
+                ("chunk_bytes", ctypes.c_size_t), ("workspace", ctypes.c_void_p),
+                ("workspace_bytes", ctypes.c_size_t), ("h2d_stream", ctypes.c_void_p),
+                ("d2h_stream", ctypes.c_void_p)]
 
 
 class OffloadStats(ctypes.Structure):
@@ -76,6 +87,8 @@ def _load():
         "pier_mu_schedule": (f32, [i64, i64]),
         "pier_outer_lr_schedule": (f32, [i64, i64]),
         "pier_outer_schedule": (i32, [i64, i64, ctypes.POINTER(OuterHP)]),
+        "pier_inner_lr_schedule": (f32, [i64, i64, f32, f32, ctypes.c_double]),
+        "pier_train_step": (i32, [vp, ctypes.POINTER(TrainCfg), i64, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -238,6 +251,20 @@ def pier_mu_schedule(t, T):
 
 def pier_outer_lr_schedule(t, T):
     return _load().pier_outer_lr_schedule(int(t), int(T))
+
+
+def pier_inner_lr_schedule(t, T, lr_max, lr_min, warmup_frac=0.02):
+    return _load().pier_inner_lr_schedule(int(t), int(T), lr_max, lr_min, warmup_frac)
+
+
+def pier_train_step(ctx, t, *, T, r, mode=PIER_MODE_PIER, lr_max, lr_min, warmup_frac=0.02, beta1, beta2, eps,
+                    weight_decay, clip_norm=0.0, chunk_bytes=0, workspace=None, h2d_stream=None,
+                    d2h_stream=None, stream=None):
+    wptr = workspace.data_ptr() if workspace is not None else None
+    wbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    cfg = TrainCfg(int(T), int(r), int(mode), lr_max, lr_min, warmup_frac, beta1, beta2, eps, weight_decay,
+                   clip_norm, int(chunk_bytes), wptr, wbytes, _stream(h2d_stream), _stream(d2h_stream))
+    _check(_load().pier_train_step(ctx.handle, ctypes.byref(cfg), int(t), _stream(stream)))
 
 
 def pier_outer_schedule(t, T):

@@ -762,6 +762,63 @@ float pier_outer_lr_schedule(int64_t t, int64_t T)
     return 0.9f;
 }
 
+float pier_inner_lr_schedule(int64_t t, int64_t T, float lr_max, float lr_min, double warmup_frac)
+{
+    const double kPi = 3.14159265358979323846;
+    const double W = warmup_frac * static_cast<double>(T);
+    if (W > 0.0 && static_cast<double>(t) <= W)
+        return static_cast<float>(static_cast<double>(lr_max) * static_cast<double>(t) / W);
+    if (t >= T) return lr_min;
+    const double ratio = (static_cast<double>(t) - W) / (static_cast<double>(T) - W);
+    const double coeff = 0.5 * (std::cos(kPi * ratio) + 1.0);
+    return static_cast<float>(static_cast<double>(lr_min) +
+                              coeff * (static_cast<double>(lr_max) - static_cast<double>(lr_min)));
+}
+
+pier_status pier_train_step(pier_ctx* c, const pier_train_cfg* cfg, int64_t t, void* hip_stream)
+{
+    if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
+    if (!cfg) return fail(PIER_ERR_INVALID_ARG, "cfg is NULL");
+    if (cfg->T < 1 || cfg->r < 1 || t < 1 || t > cfg->T)
+        return fail(PIER_ERR_INVALID_ARG, "need T >= 1, r >= 1, 1 <= t <= T (T = %lld, r = %lld, t = %lld)",
+                    static_cast<long long>(cfg->T), static_cast<long long>(cfg->r), static_cast<long long>(t));
+    if (cfg->mode != PIER_MODE_PIER && cfg->mode != PIER_MODE_DILOCO)
+        return fail(PIER_ERR_INVALID_ARG, "cfg->mode is neither PIER nor DILOCO");
+    if (!(cfg->warmup_frac >= 0.0 && cfg->warmup_frac < 1.0) || !(cfg->clip_norm >= 0.0f))
+        return fail(PIER_ERR_INVALID_ARG, "warmup_frac must lie in [0, 1) and clip_norm be >= 0");
+    pier_status st = check_all_bound(c);
+    if (st != PIER_OK) return st;
+    const bool sync = (t % cfg->r) == 0;
+    if (sync && !c->outer_bound) return fail(PIER_ERR_STATE, "anchor and momentum are not bound");
+
+    pier_adamw_hp hp;
+    hp.lr = pier_inner_lr_schedule(t, cfg->T, cfg->lr_max, cfg->lr_min, cfg->warmup_frac);
+    hp.beta1 = cfg->beta1;
+    hp.beta2 = cfg->beta2;
+    hp.eps = cfg->eps;
+    hp.weight_decay = cfg->weight_decay;
+    hp.grad_scale = 1.0f;
+    hp.step = t;
+    for (int g = 0; g < c->n_replicas; ++g) {
+        st = inner_adamw_impl(c, g, &hp, cfg->clip_norm > 0.0f, cfg->clip_norm, hip_stream);
+        if (st != PIER_OK) return st;
+    }
+    if (!sync) return PIER_OK;
+
+    pier_outer_hp ohp;
+    if (cfg->mode == PIER_MODE_DILOCO) {
+        ohp.phase = PIER_PHASE_PIER;   // no lazy start; the DiLoCo paper's recommended scalars
+        ohp.mu = 0.9f;
+        ohp.outer_lr = 0.7f;
+    } else if ((st = pier_outer_schedule(t, cfg->T, &ohp)) != PIER_OK) {
+        return st;
+    }
+    if (c->outer_loc == PIER_LOC_HOST_PINNED)
+        return pier_offload_stream(c, &ohp, cfg->chunk_bytes, cfg->workspace, cfg->workspace_bytes,
+                                   hip_stream, cfg->h2d_stream, cfg->d2h_stream, nullptr);
+    return pier_outer_step(c, &ohp, hip_stream);
+}
+
 pier_status pier_outer_schedule(int64_t t, int64_t T, pier_outer_hp* out)
 {
     if (!out) return fail(PIER_ERR_INVALID_ARG, "out is NULL");

@@ -188,6 +188,39 @@ class Run:
                 if self.oW is not None:
                     self.oW[g] = O.to_bf16(self.oP[g])
 
+    def train_steps(self, n, *, T, r, diloco=False, lr_max, lr_min, warmup_frac=0.02, clip=0.0):
+        """n iterations through pier_train_step (inner steps with the scheduled learning rate,
+        optional clipping, outer step every r iterations with the scheduled scalars), mirrored
+        step by step with the oracle's own schedule functions."""
+        hp = {k: self.hp[k] for k in ("beta1", "beta2", "eps", "weight_decay")}
+        self.sync_log = []
+        for _ in range(n):
+            self.t += 1
+            t = self.t
+            t_sync = -(-t // r) * r                              # the synchronisation that ends this round
+            lazy = (not diloco) and O.phase(min(t_sync, T), T) == O.WARMUP
+            lr = O.inner_lr(t, T, lr_max, lr_min, warmup_frac)
+            for g in range(self.G):
+                self.Gd[g].fill_normal(seed=self.seed, stream=0 if lazy else g, step=t, std=self.grad_std,
+                                       hip_stream=self.stream)
+            gs = [self._take(self.Gd[g].flat) for g in range(self.G)]
+            kw = dict(workspace=self.workspace, chunk_bytes=self.chunk_bytes, h2d_stream=self.s_in,
+                      d2h_stream=self.s_out) if self.offload else {}
+            pier.pier_train_step(self.ctx, t, T=T, r=r, mode=pier.PIER_MODE_DILOCO if diloco else pier.PIER_MODE_PIER,
+                                 lr_max=lr_max, lr_min=lr_min, warmup_frac=warmup_frac, clip_norm=clip,
+                                 stream=self.stream, **hp, **kw)
+            for g in range(self.G):
+                coef = O.clip_coef(self._oracle_sumsq(g), clip) if clip > 0 else 1.0
+                O.adamw(self.oP[g], self.oM1[g], self.oV[g], gs[g], step=t, lr=lr, grad_scale=coef, **hp)
+                if self.oW is not None:
+                    self.oW[g] = O.to_bf16(self.oP[g])
+            if t % r == 0:
+                ph, mu, lr_o = (O.PIER, 0.9, 0.7) if diloco else O.outer_scalars(t, T)
+                O.outer(self.oP, self.oA, self.oMo, mu=mu, lr=lr_o, phase=ph)
+                if self.oW is not None and ph == O.PIER:
+                    self.oW = [O.to_bf16(p) for p in self.oP]
+                self.sync_log.append((t, ph, round(mu, 4), lr_o))
+
     def outer(self, *, mu, lr, phase):
         if self.offload:
             self.stats = pier.pier_offload_stream(self.ctx, outer_lr=lr, mu=mu, phase=phase,

@@ -58,6 +58,15 @@ def test_schedule_helpers_agree_with_the_oracle_everywhere():
             assert pier.pier_outer_lr_schedule(t, T) == O.outer_lr(t, T)
 
 
+def test_inner_lr_helper_agrees_with_the_oracle():
+    from oracle import pier_oracle as O
+    for T, lr_max, lr_min, wf in ((100_000, 4e-4, 4e-5, 0.02), (40, 3e-4, 3e-5, 0.1), (1000, 1.5e-4, 1.5e-5, 0.0)):
+        ts = range(1, T + 2) if T <= 1000 else list(range(1, 4000, 3)) + list(range(4000, T + 2, 331))
+        for t in ts:
+            assert pier.pier_inner_lr_schedule(t, T, lr_max, lr_min, wf) == O.inner_lr(t, T, lr_max, lr_min, wf), t
+    assert pier.pier_inner_lr_schedule(2000, 100_000, 4e-4, 4e-5) == pytest.approx(4e-4, rel=1e-6)   # Table I
+
+
 def test_host_side_argument_errors():
     with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
         pier.pier_ctx_create([], 1)
@@ -82,6 +91,13 @@ def test_host_side_argument_errors():
         pier.pier_inner_adamw(ctx, 0, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, step=1)
     with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):
         pier.pier_outer_step(ctx, outer_lr=0.7, mu=0.9, phase=1)
+    tc = dict(T=100, r=10, lr_max=1e-3, lr_min=1e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):
+        pier.pier_train_step(ctx, 1, **tc)                     # nothing bound
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_train_step(ctx, 0, **tc)
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_train_step(ctx, 1, **dict(tc, r=0))
     assert pier.pier_offload_workspace_bytes(ctx, 1 << 20) == 2 * 64      # 16 floats round up to one 64-byte piece
     with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
         pier.pier_offload_workspace_bytes(ctx, 100)

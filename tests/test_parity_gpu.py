@@ -161,6 +161,42 @@ def test_bf16_working_copies_offload_and_partial_binding():
     assert np.array_equal(before["W0"], res._take(old_w[0].flat))      # no longer written
 
 
+# ------------------------------------------------------------------ whole schedule
+
+@pytest.mark.parametrize("diloco,offload", [(False, False), (True, False), (False, True)])
+def test_train_step_runs_the_whole_schedule(diloco, offload):
+    """T = 40 iterations, r = 4: lazy start (t <= 4), mu 0.99 (t = 4 is lazy; 8 would be 0.9 ...) -
+    every phase of the schedule through pier_train_step, with clipping, cosine inner learning
+    rate and bf16 working copies, against the oracle's step-by-step mirror."""
+    H_ = _harness()
+    _log("train_step diloco=%d offload=%d" % (diloco, offload))
+    numels = [4096, 1000, 36, 0, 70_000] if offload else RAGGED + [50_000]
+    r = H_.Run(numels, 2, seed=37, shadow=True, offload=offload, chunk_bytes=65536 if offload else None)
+    T = 40
+    r.train_steps(T, T=T, r=4, diloco=diloco, lr_max=3e-4, lr_min=3e-5, warmup_frac=0.1, clip=0.1)
+    rep = r.check("train_step")
+    phases = [(t, ph, mu) for t, ph, mu, _ in r.sync_log]
+    if diloco:
+        assert all(ph == PIER and mu == 0.9 and lr == 0.7 for _, ph, mu, lr in r.sync_log)
+    else:
+        assert phases[:5] == [(4, WARMUP, 0.9), (8, PIER, 0.9), (12, PIER, 0.9), (16, PIER, 0.9), (20, PIER, 0.9)]
+        assert [lr for *_, lr in r.sync_log][1:4] == pytest.approx([1.1, 1.1, 1.1])
+        assert r.sync_log[-1][3] == pytest.approx(0.9)          # last 20 %
+    _log("train_step: %s" % rep)
+
+
+def test_train_step_mu_bands():
+    """T = 400, r = 10: synchronisations at t = 40 (lazy start), 50 (mu 0.99, lr 0.25), 60 (0.95, 0.5),
+    70 (0.95, 0.75), 80 (0.9, 1.1): the momentum-decay bands and the outer-lr ramp."""
+    H_ = _harness()
+    r = H_.Run([5000, 24, 3], 2, seed=41)
+    r.train_steps(80, T=400, r=10, lr_max=4e-4, lr_min=4e-5)
+    r.check("mu bands")
+    got = [(t, ph, mu, round(lr, 4)) for t, ph, mu, lr in r.sync_log]
+    assert got == [(10, WARMUP, 0.9, 0.0), (20, WARMUP, 0.9, 0.0), (30, WARMUP, 0.9, 0.0), (40, WARMUP, 0.9, 0.0),
+                   (50, PIER, 0.99, 0.25), (60, PIER, 0.95, 0.5), (70, PIER, 0.95, 0.75), (80, PIER, 0.9, 1.1)]
+
+
 # ------------------------------------------------------------------ gradient clipping
 
 def _check_clip_log(r, expect_active):
