@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-arena", action="store_true", help="plain allocations instead of the probed arena")
     ap.add_argument("--chunk-mib", type=int, default=256, help="offload piece size")
+    ap.add_argument("--variants", action="store_true",
+                    help="also time the clipped step, the bf16-working-copy kernels and the lazy-start outer step")
     return ap.parse_args()
 
 
@@ -185,6 +187,49 @@ def main():
                            "algorithmic_GB_per_launch": outer_bpe * N / 1e9,
                            "bytes_per_param": outer_bpe, "avg_launch_ms": outer_ms, "launches_timed": K},
     }
+
+    if args.variants:
+        def timed(fn, n):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            fn()
+            e0.record(stream)
+            for _ in range(n):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        def all_replicas(call):
+            def f():
+                t_step[0] += 1
+                for g in range(G):
+                    call(g)
+            return f
+
+        var = {}
+        ms = timed(all_replicas(lambda g: pier.pier_inner_adamw_clipped(ctx, g, step=t_step[0], max_norm=1.0,
+                                                                       stream=stream, **hp)), 3) / G
+        var["adamw_clipped"] = {"ms": ms, "bytes_per_param": gbytes + (2 if bf16 else 4),
+                                "GBps": (gbytes + (2 if bf16 else 4)) * N / ms / 1e6}
+        ms = timed(lambda: pier.pier_outer_step(ctx, outer_lr=lr_o, mu=mu, phase=pier.PIER_PHASE_WARMUP,
+                                                stream=stream), 3)
+        var["outer_lazy_start"] = {"ms": ms, "bytes_per_param": 4 * G + 16, "GBps": (4 * G + 16) * N / ms / 1e6}
+        Wb = []
+        for g in range(G):
+            flat = arena.alloc(N, torch.bfloat16, P[g].cls)[0] if arena is not None else \
+                torch.empty(N, dtype=torch.bfloat16, device="cuda")
+            Wb.append([flat[s0:s0 + n] for s0, n in zip(P[g].starts, w.numels)])
+            pier.pier_bind_shadow(ctx, g, Wb[g])
+        ms = timed(all_replicas(lambda g: pier.pier_inner_adamw(ctx, g, step=t_step[0], stream=stream, **hp)), 3) / G
+        var["adamw_bf16_working_copy"] = {"ms": ms, "bytes_per_param": gbytes + 2, "GBps": (gbytes + 2) * N / ms / 1e6}
+        ms = timed(lambda: pier.pier_outer_step(ctx, outer_lr=lr_o, mu=mu, phase=pier.PIER_PHASE_PIER,
+                                                stream=stream), 3)
+        var["outer_bf16_working_copy"] = {"ms": ms, "bytes_per_param": outer_bpe + 2 * G,
+                                          "GBps": (outer_bpe + 2 * G) * N / ms / 1e6}
+        for g in range(G):
+            pier.pier_bind_shadow(ctx, g, None)
+        del Wb
+        out["variants"] = var
 
     if not args.no_offload:
         # the same outer step with anchor and M streamed from pinned host memory
