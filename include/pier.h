@@ -72,9 +72,10 @@ int64_t pier_ctx_numel(const pier_ctx* ctx);
 /* Launch shape of the kernels; defaults suit MI355X and results never depend on it.
  * chunk_elems: elements one workgroup handles per chunk (multiple of 1024, >= 1024);
  * unroll: 128-bit loads each lane keeps in flight per stream (1, 2 or 4);
- * max_grid: cap on workgroups per launch (0 = one chunk per workgroup);
- * nontemporal: 1 = mark loads/stores as streaming.  Pass 0 / -1 (nontemporal) to keep
- * a field unchanged.  Must be called before the first bind. */
+ * max_grid: cap on workgroups per launch (0 = no cap: one chunk per workgroup; always
+ * taken as given); nontemporal: 1 = mark loads/stores as streaming.  chunk_elems = 0,
+ * unroll = 0, nontemporal = -1 keep that field unchanged.  Must be called before the
+ * first bind. */
 pier_status pier_ctx_set_launch(pier_ctx* ctx, int64_t chunk_elems, int unroll, int max_grid,
                                 int nontemporal);
 

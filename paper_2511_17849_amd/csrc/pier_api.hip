@@ -113,16 +113,24 @@ void build_chunks(const pier_ctx* c, int64_t lo, int64_t hi, std::vector<Chunk>&
     }
 }
 
-pier_status ensure_device(pier_ctx* c)
+void release_tables(pier_ctx* c)
 {
-    int dev = -1;
-    PIER_HIP(hipGetDevice(&dev));
-    if (c->device >= 0) {
-        if (dev != c->device)
-            return fail(PIER_ERR_STATE, "context belongs to device %d but device %d is current",
-                        c->device, dev);
-        return PIER_OK;
-    }
+    if (c->d_chunks) (void)hipFree(c->d_chunks);
+    if (c->d_rep) (void)hipFree(c->d_rep);
+    if (c->d_rows) (void)hipFree(c->d_rows);
+    if (c->d_partials) (void)hipFree(c->d_partials);
+    if (c->d_clip) (void)hipFree(c->d_clip);
+    if (c->offload_done) (void)hipEventDestroy(c->offload_done);
+    c->d_chunks = nullptr;
+    c->d_rep = nullptr;
+    c->d_rows = nullptr;
+    c->d_partials = nullptr;
+    c->d_clip = nullptr;
+    c->offload_done = nullptr;
+}
+
+pier_status allocate_tables(pier_ctx* c)
+{
     c->h_chunks.clear();
     build_chunks(c, 0, c->N, c->h_chunks);
     if (c->h_chunks.size() > static_cast<size_t>(INT32_MAX))
@@ -144,6 +152,26 @@ pier_status ensure_device(pier_ctx* c)
     PIER_HIP(hipMalloc(reinterpret_cast<void**>(&c->d_clip), sizeof(ClipState) * c->n_replicas));
     PIER_HIP(hipMemset(c->d_clip, 0, sizeof(ClipState) * c->n_replicas));
     PIER_HIP(hipEventCreate(&c->offload_done));
+    return PIER_OK;
+}
+
+// First GPU contact of a context: remembers the current device and creates the tables
+// there (all of them, or none if any allocation fails).
+pier_status ensure_device(pier_ctx* c)
+{
+    int dev = -1;
+    PIER_HIP(hipGetDevice(&dev));
+    if (c->device >= 0) {
+        if (dev != c->device)
+            return fail(PIER_ERR_STATE, "context belongs to device %d but device %d is current",
+                        c->device, dev);
+        return PIER_OK;
+    }
+    const pier_status st = allocate_tables(c);
+    if (st != PIER_OK) {
+        release_tables(c);
+        return st;
+    }
     c->device = dev;
     return PIER_OK;
 }
@@ -278,13 +306,8 @@ pier_status pier_ctx_destroy(pier_ctx* c)
 {
     if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
     if (c->device >= 0) {
-        if (c->d_chunks) (void)hipFree(c->d_chunks);
-        if (c->d_rep) (void)hipFree(c->d_rep);
-        if (c->d_rows) (void)hipFree(c->d_rows);
-        if (c->d_partials) (void)hipFree(c->d_partials);
-        if (c->d_clip) (void)hipFree(c->d_clip);
+        release_tables(c);
         for (auto& kv : c->plans) free_plan(kv.second);
-        if (c->offload_done) (void)hipEventDestroy(c->offload_done);
     }
     delete c;
     return PIER_OK;
