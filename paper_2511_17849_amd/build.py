@@ -28,6 +28,21 @@ def build(verbose=False):
     return LIB
 
 
+def build_abi_client(verbose=False):
+    """The plain C-ABI client used by the GPU tests (tests/abi_client): links libpier.so,
+    uses no torch."""
+    root = os.path.dirname(HERE)
+    src = os.path.join(root, "tests", "abi_client", "pier_client.cpp")
+    exe = os.path.join(root, "tests", "abi_client", "pier_client")
+    cmd = [HIPCC, "-O2", "-std=c++17", "--offload-arch=gfx950", "-o", exe, src,
+           "-L" + HERE, "-lpier", "-Wl,-rpath,$ORIGIN/../../paper_2511_17849_amd"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return exe
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_abi_client(verbose=True))
     sys.exit(0)

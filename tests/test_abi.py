@@ -30,6 +30,16 @@ def test_library_is_built_and_exports_every_declared_symbol():
         assert hasattr(lib, n), "libpier.so does not export " + n
 
 
+def test_header_is_plain_c(tmp_path):
+    """include/pier.h compiles as C99 on its own (no C++, no HIP, no torch types)."""
+    import subprocess
+    src = tmp_path / "use_pier.c"
+    src.write_text('#include "pier.h"\nint main(void) { pier_outer_hp hp; pier_train_cfg c; (void)hp; (void)c; '
+                   'return pier_status_string(PIER_OK) == 0; }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           "-c", str(src), "-o", str(tmp_path / "use_pier.o")])
+
+
 def test_binding_covers_the_header():
     for n in declared_functions():
         assert hasattr(pier, n), "binding lacks " + n

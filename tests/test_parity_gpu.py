@@ -361,6 +361,49 @@ def test_argument_errors_are_reported_not_launched():
             assert float(t_.abs().sum()) == 0.0
 
 
+def test_plain_c_client_of_the_abi(tmp_path):
+    """A client that uses nothing but the C ABI, hipMalloc'd tensors and HIP streams (no torch):
+    inner steps, the resident outer step, then the host-offload outer step; every buffer it
+    writes back is compared with the oracle run on the same case."""
+    import os
+    import subprocess
+    from oracle import pier_oracle as O
+    exe = os.path.join(os.path.dirname(__file__), "abi_client", "pier_client")
+    assert os.path.exists(exe), "build with __graft_entry__.build()"
+    rng = np.random.default_rng(43)
+    numel, G, H = [5000, 7, 0, 1025, 4096], 2, 3
+    N = sum(numel)
+    theta0 = rng.normal(0, 0.02, N).astype(np.float32)
+    grads = rng.normal(0, 1e-3, (2, H, G, N)).astype(np.float32)
+    case, result = tmp_path / "case.bin", tmp_path / "result.bin"
+    with open(case, "wb") as f:
+        np.array([len(numel), G, H], np.int32).tofile(f)
+        np.array(numel, np.int64).tofile(f)
+        theta0.tofile(f)
+        grads.tofile(f)
+    _log("running %s" % exe)
+    out = subprocess.run([exe, str(case), str(result)], capture_output=True, text=True, timeout=100)
+    assert out.returncode == 0, out.stderr
+    got = np.fromfile(result, np.float32).reshape(3 * G + 2, N)
+    hp = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    P = [theta0.copy() for _ in range(G)]
+    M1 = [np.zeros(N, np.float32) for _ in range(G)]
+    V = [np.zeros(N, np.float32) for _ in range(G)]
+    a, Mo = theta0.copy(), np.zeros(N, np.float32)
+    t = 0
+    for rnd, lr_o in ((0, 0.7), (1, 1.1)):
+        for h in range(H):
+            t += 1
+            for g in range(G):
+                O.adamw(P[g], M1[g], V[g], np.ascontiguousarray(grads[rnd, h, g]), step=t, **hp)
+        O.outer(P, a, Mo, mu=0.9, lr=lr_o, phase=O.PIER)
+    H_ = _harness()
+    want = [x for g in range(G) for x in (P[g], M1[g], V[g])] + [a, Mo]
+    for k, (g_, w_) in enumerate(zip(got, want)):
+        assert H_.tol_ok(g_, w_).all(), k
+        assert np.array_equal(g_, w_), k           # and in fact bit for bit
+
+
 def test_all_empty_model_is_a_no_op():
     import paper_2511_17849_amd as pier
     ctx = pier.pier_ctx_create([0, 0], 1)
