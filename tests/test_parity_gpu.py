@@ -114,6 +114,36 @@ def test_grad_scale_and_other_hyperparameters():
     r.check("grad_scale")
 
 
+@pytest.mark.parametrize("case", range(8))
+def test_randomised_small_cases(case):
+    """Seeded random tensor lists (odd sizes, empty tensors, sizes around chunk multiples), group
+    counts 1..16, launch shapes, gradient dtype, padding, phase sequence and scalars."""
+    H_ = _harness()
+    rng = np.random.default_rng(1000 + case)
+    nt = int(rng.integers(1, 12))
+    pool = [0, 1, 2, 3, 4, 5, 255, 256, 1023, 1024, 1025, 4095, 4096, 4100, 12289, 65536 + 3]
+    numels = [int(rng.choice(pool)) if rng.random() < 0.7 else int(rng.integers(1, 200_000)) for _ in range(nt)]
+    if sum(numels) == 0:
+        numels.append(17)
+    G = int(rng.choice([1, 2, 3, 4, 6, 7, 8, 9, 16]))
+    launch = dict(chunk_elems=int(rng.choice([1024, 2048, 4096, 16384])), unroll=int(rng.choice([1, 2, 4])),
+                  max_grid=int(rng.choice([0, 0, 5, 64])), nontemporal=int(rng.choice([0, 1])))
+    bf16 = bool(rng.integers(0, 2))
+    pad = int(rng.integers(0, 2))
+    shadow = bool(rng.integers(0, 2))
+    hp = dict(lr=float(rng.choice([1e-4, 3e-4, 1e-3])), beta1=0.9, beta2=float(rng.choice([0.95, 0.999])),
+              eps=1e-8, weight_decay=float(rng.choice([0.0, 0.1])))
+    _log("random case %d: numels=%s G=%d launch=%s bf16=%d pad=%d shadow=%d" % (case, numels, G, launch, bf16, pad, shadow))
+    r = H_.Run(numels, G, grad_bf16=bf16, hp=hp, pad=pad, launch=launch, seed=case, shadow=shadow)
+    for _ in range(int(rng.integers(1, 4))):
+        phase = int(rng.integers(0, 2))
+        r.inner_steps(int(rng.integers(1, 4)), shared_stream=(phase == WARMUP),
+                      clip=float(rng.choice([0.02, 0.5])) if rng.random() < 0.5 else None)
+        r.outer(mu=float(rng.choice([0.0, 0.9, 0.95, 0.99])), lr=float(rng.choice([0.25, 0.7, 1.0, 1.1])), phase=phase)
+        rep = r.check("random case %d" % case)
+    assert rep["bit_exact"]
+
+
 # ------------------------------------------------------------------ bf16 working weights
 
 @pytest.mark.parametrize("G,pad", [(1, 0), (2, 1), (3, 0), (8, 0)])
