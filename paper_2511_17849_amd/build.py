@@ -42,7 +42,19 @@ def build_abi_client(verbose=False):
     return exe
 
 
+def build_stream_bench(verbose=False):
+    """The stand-alone HBM streaming reference (csrc/hbm_stream_bench.hip)."""
+    exe = os.path.join(HERE, "hbm_stream_bench")
+    cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-o", exe, os.path.join(CSRC, "hbm_stream_bench.hip")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return exe
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
     print(build_abi_client(verbose=True))
+    print(build_stream_bench(verbose=True))
     sys.exit(0)
