@@ -58,8 +58,14 @@ def _load():
     if _lib is not None:
         return _lib
     if not os.path.exists(_LIB_PATH):
-        raise ImportError("libpier.so is not built: run `python -m paper_2511_17849_amd.build` "
-                          "(or __graft_entry__.build()); there is no fallback path")
+        # nothing built yet: build once (hipcc cross-compiles without a GPU); there is no
+        # other implementation to fall back to, so a failed build is a hard error
+        try:
+            from . import build as _build
+            _build.build()
+        except Exception as e:
+            raise ImportError("libpier.so is not built and building it failed (%s): run "
+                              "`python -m paper_2511_17849_amd.build`; there is no fallback path" % e)
     # torch ships its own HIP runtime; import it first so that libpier binds to the
     # runtime that owns torch's allocations and streams
     import torch  # noqa: F401

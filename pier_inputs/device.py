@@ -16,7 +16,8 @@ def _load():
     global _lib
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
-            raise ImportError("libpier_inputs.so is not built: run `python -m pier_inputs.build`")
+            from . import build as _build      # nothing built yet: build once
+            _build.build()
         L = ctypes.CDLL(_LIB_PATH)
         L.pier_inputs_fill_normal.restype = ctypes.c_int
         L.pier_inputs_fill_normal.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
