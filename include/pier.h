@@ -79,6 +79,16 @@ int64_t pier_ctx_numel(const pier_ctx* ctx);
 pier_status pier_ctx_set_launch(pier_ctx* ctx, int64_t chunk_elems, int unroll, int max_grid,
                                 int nontemporal);
 
+/* Optional: how many wavefronts the kernels keep resident (tuning only, results do not
+ * change).  wg_threads: 256 = one four-wave workgroup per chunk, 64 = four one-wave
+ * workgroups per chunk (then one vector per lane per stream, whatever `unroll` says),
+ * 0 = each kernel's measured best (64 unless unroll or max_grid were set);
+ * lds_bytes: LDS reserved per workgroup and left unused, which caps the workgroups a
+ * compute unit holds at floor(160 KiB / lds_bytes) (0 = no cap; at most 65536),
+ * -1 = each kernel's measured best (12 waves per compute unit for the AdamW step, 8
+ * for the outer step).  Default: 0, -1.  May be called at any time between launches. */
+pier_status pier_ctx_set_occupancy(pier_ctx* ctx, int wg_threads, int lds_bytes);
+
 /* Binds replica `replica` (0-based).  p, m, v, grad are HOST arrays of n_tensors
  * DEVICE pointers: parameters theta_g, AdamW first and second moments (fp32), and
  * the gradient of each tensor, fp32 or (grad_is_bf16 != 0) bfloat16.  A tensor with

@@ -79,6 +79,7 @@ def _load():
         "pier_ctx_destroy": (i32, [vp]),
         "pier_ctx_numel": (i64, [vp]),
         "pier_ctx_set_launch": (i32, [vp, i64, i32, i32, i32]),
+        "pier_ctx_set_occupancy": (i32, [vp, i32, i32]),
         "pier_bind_replica": (i32, [vp, i32, pp, pp, pp, pp, i32]),
         "pier_bind_shadow": (i32, [vp, i32, pp]),
         "pier_bind_outer": (i32, [vp, i32, pp, pp]),
@@ -174,6 +175,10 @@ def pier_ctx_numel(ctx):
 def pier_ctx_set_launch(ctx, chunk_elems=0, unroll=0, max_grid=0, nontemporal=-1):
     _check(_load().pier_ctx_set_launch(ctx.handle, int(chunk_elems), int(unroll), int(max_grid),
                                        int(nontemporal)))
+
+
+def pier_ctx_set_occupancy(ctx, wg_threads=0, lds_bytes=-1):
+    _check(_load().pier_ctx_set_occupancy(ctx.handle, int(wg_threads), int(lds_bytes)))
 
 
 def pier_bind_replica(ctx, replica, p, m, v, grad, grad_is_bf16=False):

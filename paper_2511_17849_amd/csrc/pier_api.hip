@@ -63,7 +63,7 @@ struct pier_ctx {
     // 1024-element tile per stream with streaming (nt) accesses, sustain the highest
     // HBM rate for both kernels; larger chunks or deeper unrolling are 1-5% slower.
     int64_t chunk_elems = 1024;
-    LaunchShape shape{1, 0, 1};
+    LaunchShape shape{1, 0, 1, 0, -1};
 
     int device = -1;  // set by the first call that touches the GPU
     std::vector<Chunk> h_chunks;
@@ -334,6 +334,18 @@ pier_status pier_ctx_set_launch(pier_ctx* c, int64_t chunk_elems, int unroll, in
     if (unroll) c->shape.unroll = unroll;
     c->shape.max_grid = max_grid;
     if (nontemporal >= 0) c->shape.nontemporal = nontemporal;
+    return PIER_OK;
+}
+
+pier_status pier_ctx_set_occupancy(pier_ctx* c, int wg_threads, int lds_bytes)
+{
+    if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
+    if (wg_threads != 0 && wg_threads != 64 && wg_threads != kBlock)
+        return fail(PIER_ERR_INVALID_ARG, "wg_threads = %d: need 64, %d or 0", wg_threads, kBlock);
+    if (lds_bytes < -1 || lds_bytes > 65536)
+        return fail(PIER_ERR_INVALID_ARG, "lds_bytes = %d: need 0 .. 65536, or -1", lds_bytes);
+    c->shape.wg_threads = wg_threads;
+    c->shape.lds_bytes = lds_bytes;
     return PIER_OK;
 }
 

@@ -41,12 +41,14 @@ struct AdamwScalars {
 };
 
 struct LaunchShape {
-    int unroll;       // 1, 2 or 4
-    int max_grid;     // 0 = one chunk per workgroup
+    int unroll;       // 1, 2 or 4 vectors per lane per stream (workgroups of kBlock threads only)
+    int max_grid;     // 0 = one chunk per team of kBlock lanes
     int nontemporal;  // 0 / 1
+    int wg_threads;   // kBlock, or 64: a team is four one-wave workgroups; 0 = the kernel's best
+    int lds_bytes;    // unused dynamic LDS per workgroup: caps the workgroups resident per CU; -1 = the kernel's best
 };
 
-constexpr int kBlock = 256;  // four 64-wide wavefronts
+constexpr int kBlock = 256;  // lanes that share one chunk: four 64-wide wavefronts
 
 // Result of the gradient-norm pass of one replica (device memory).
 struct ClipState {

@@ -85,6 +85,25 @@ __device__ __forceinline__ vushort4 f32_to_bf16(vfloat4 f)
     return r;
 }
 
+// A chunk is always worked on by a team of kBlock lanes.  The team is one workgroup of
+// kBlock threads, or kBlock / WG consecutive smaller workgroups (WG = 64: four one-wave
+// workgroups), which the dispatcher deals to different XCDs and which retire one by one;
+// the addresses each lane touches are the same either way.
+template <int WG>
+struct Team {
+    static_assert(WG == 64 || WG == kBlock, "workgroups of one wave or of a whole team");
+    static constexpr int kSplit = kBlock / WG;
+    int lane;    // position of this thread among the kBlock lanes of its team
+    int first;   // first chunk of the team
+    int stride;  // teams in the grid
+    __device__ __forceinline__ Team()
+        : lane(static_cast<int>(blockIdx.x % kSplit) * WG + static_cast<int>(threadIdx.x)),
+          first(static_cast<int>(blockIdx.x / kSplit)),
+          stride(static_cast<int>(gridDim.x / kSplit))
+    {
+    }
+};
+
 // ------------------------------------------------------------------ inner AdamW
 //
 // AdamW with decoupled weight decay and bias correction (the inner optimizer of
@@ -151,21 +170,22 @@ __device__ __forceinline__ void adamw_scalar(float* p, float* m, float* v, const
     if constexpr (SHADOW) st<false>(w, f32_to_bf16(pi));
 }
 
-template <int UNROLL, bool BF16, bool NT, bool SHADOW>
-__global__ __launch_bounds__(kBlock) void adamw_kernel(const Chunk* __restrict__ chunks,
-                                                       int n_chunks,
-                                                       const RepPtrs* __restrict__ tab,
-                                                       const ClipState* __restrict__ clip,
-                                                       AdamwScalars s)
+template <int WG, int UNROLL, bool BF16, bool NT, bool SHADOW>
+__global__ __launch_bounds__(WG) void adamw_kernel(const Chunk* __restrict__ chunks,
+                                                   int n_chunks,
+                                                   const RepPtrs* __restrict__ tab,
+                                                   const ClipState* __restrict__ clip,
+                                                   AdamwScalars s)
 {
     // gradient clipping: the coefficient of the norm pass that ran before this launch
     if (clip) s.grad_scale = s.grad_scale * clip->coef;
     typedef typename GradVec<BF16>::type gvec;
     typedef typename std::conditional<BF16, unsigned short, float>::type gscalar;
-    const int tid = threadIdx.x;
+    const Team<WG> team;
+    const int tid = team.lane;
     constexpr int kTile = kBlock * UNROLL;  // vectors per tile
 
-    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    for (int c = team.first; c < n_chunks; c += team.stride) {
         const Chunk ch = chunks[c];
         const RepPtrs t = tab[ch.tensor];
         float* __restrict__ p = t.p + ch.off;
@@ -232,13 +252,31 @@ static int grid_for(int n_chunks, const LaunchShape& shape)
     return n_chunks;
 }
 
-template <int U, bool BF16, bool SHADOW>
-static void adamw_dispatch_nt(int grid, const Chunk* chunks, int n_chunks, const RepPtrs* tab,
-                              const ClipState* clip, const AdamwScalars& s, bool nt, hipStream_t stream)
+// Fills in the fields of a launch shape left on "auto".  Measured on MI355X at GPT-2
+// small .. 7B sizes: both kernels stream fastest with one-wave workgroups and only as
+// many waves resident as their arithmetic needs to hide its own latency (more waves in
+// flight spread the DRAM traffic over more open pages and read/write turnarounds):
+// 12 waves per compute unit for AdamW (three divisions and a square root per element),
+// 8 for the outer step.  The cap is an unused LDS reservation per workgroup.
+static LaunchShape resolved(LaunchShape shape, int auto_lds)
 {
-    if (nt) hipLaunchKernelGGL((adamw_kernel<U, BF16, true, SHADOW>), dim3(grid), dim3(kBlock), 0, stream,
-                               chunks, n_chunks, tab, clip, s);
-    else hipLaunchKernelGGL((adamw_kernel<U, BF16, false, SHADOW>), dim3(grid), dim3(kBlock), 0, stream,
+    if (shape.wg_threads == 0) shape.wg_threads = (shape.unroll == 1 && shape.max_grid == 0) ? 64 : kBlock;
+    if (shape.lds_bytes < 0) shape.lds_bytes = shape.wg_threads == 64 ? auto_lds : 0;
+    return shape;
+}
+constexpr int kAdamwAutoLds = 13 * 1024;  // floor(160 KiB / 13 KiB) = 12 one-wave workgroups per CU
+constexpr int kOuterAutoLds = 18 * 1024;  // 8 per CU
+
+template <int WG, int U, bool BF16, bool SHADOW>
+static void adamw_dispatch_nt(int grid, const Chunk* chunks, int n_chunks, const RepPtrs* tab,
+                              const ClipState* clip, const AdamwScalars& s, const LaunchShape& shape,
+                              hipStream_t stream)
+{
+    const dim3 g(static_cast<unsigned>(grid) * (kBlock / WG)), b(WG);
+    const unsigned lds = static_cast<unsigned>(shape.lds_bytes);
+    if (shape.nontemporal) hipLaunchKernelGGL((adamw_kernel<WG, U, BF16, true, SHADOW>), g, b, lds, stream,
+                                              chunks, n_chunks, tab, clip, s);
+    else hipLaunchKernelGGL((adamw_kernel<WG, U, BF16, false, SHADOW>), g, b, lds, stream,
                             chunks, n_chunks, tab, clip, s);
 }
 
@@ -247,19 +285,23 @@ static void adamw_dispatch_u(int grid, const Chunk* chunks, int n_chunks, const 
                              const ClipState* clip, const AdamwScalars& s, const LaunchShape& shape,
                              hipStream_t stream)
 {
-    const bool nt = shape.nontemporal != 0;
+    if (shape.wg_threads == 64) {   // one-wave workgroups: one vector per lane per stream only
+        adamw_dispatch_nt<64, 1, BF16, SHADOW>(grid, chunks, n_chunks, tab, clip, s, shape, stream);
+        return;
+    }
     switch (shape.unroll) {
-    case 1: adamw_dispatch_nt<1, BF16, SHADOW>(grid, chunks, n_chunks, tab, clip, s, nt, stream); break;
-    case 2: adamw_dispatch_nt<2, BF16, SHADOW>(grid, chunks, n_chunks, tab, clip, s, nt, stream); break;
-    default: adamw_dispatch_nt<4, BF16, SHADOW>(grid, chunks, n_chunks, tab, clip, s, nt, stream); break;
+    case 1: adamw_dispatch_nt<kBlock, 1, BF16, SHADOW>(grid, chunks, n_chunks, tab, clip, s, shape, stream); break;
+    case 2: adamw_dispatch_nt<kBlock, 2, BF16, SHADOW>(grid, chunks, n_chunks, tab, clip, s, shape, stream); break;
+    default: adamw_dispatch_nt<kBlock, 4, BF16, SHADOW>(grid, chunks, n_chunks, tab, clip, s, shape, stream); break;
     }
 }
 
 hipError_t launch_adamw(const Chunk* chunks, int n_chunks, const RepPtrs* tab, bool grad_bf16,
                         bool shadow, const AdamwScalars& s, const ClipState* clip,
-                        const LaunchShape& shape, hipStream_t stream)
+                        const LaunchShape& requested, hipStream_t stream)
 {
     if (n_chunks <= 0) return hipSuccess;
+    const LaunchShape shape = resolved(requested, kAdamwAutoLds);
     const int grid = grid_for(n_chunks, shape);
     if (grad_bf16) {
         if (shadow) adamw_dispatch_u<true, true>(grid, chunks, n_chunks, tab, clip, s, shape, stream);
@@ -472,17 +514,18 @@ struct OuterRow {
 
 // The tables are separate const __restrict__ parameters: only then may the compiler
 // read them through the scalar unit (they are never written by a kernel).
-template <int G, int UNROLL, bool FLAT, bool PIER, bool NT, bool SHADOW>
-__global__ __launch_bounds__(kBlock) void outer_kernel(const Chunk* __restrict__ chunks,
-                                                       const OuterRow<G>* __restrict__ rows,
-                                                       OuterArgs A)
+template <int WG, int G, int UNROLL, bool FLAT, bool PIER, bool NT, bool SHADOW>
+__global__ __launch_bounds__(WG) void outer_kernel(const Chunk* __restrict__ chunks,
+                                                   const OuterRow<G>* __restrict__ rows,
+                                                   OuterArgs A)
 {
     static_assert(sizeof(OuterRow<G>) == (kOuterRowHead + 2 * G) * 8, "row layout");
     static_assert(PIER || !SHADOW, "the lazy-start phase does not touch the replicas");
-    const int tid = threadIdx.x;
+    const Team<WG> team;
+    const int tid = team.lane;
     constexpr int kTile = kBlock * UNROLL;
 
-    for (int c = blockIdx.x; c < A.n_chunks; c += gridDim.x) {
+    for (int c = team.first; c < A.n_chunks; c += team.stride) {
         const Chunk ch = chunks[c];
         const OuterRow<G> row = rows[ch.tensor];
         float* __restrict__ a;
@@ -621,36 +664,41 @@ struct OuterTables {
     const uint64_t* rows;
 };
 
-template <int G, int U, bool FLAT, bool PIER, bool SHADOW>
-static void outer_launch(int grid, const OuterTables& T, const OuterArgs& A, bool nt, hipStream_t stream)
+template <int WG, int G, int U, bool FLAT, bool PIER, bool SHADOW>
+static void outer_launch(int grid, const OuterTables& T, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
 {
     const OuterRow<G>* ROWS = reinterpret_cast<const OuterRow<G>*>(T.rows);
-    if (nt) hipLaunchKernelGGL((outer_kernel<G, U, FLAT, PIER, true, SHADOW>), dim3(grid), dim3(kBlock), 0, stream, T.chunks, ROWS, A);
-    else hipLaunchKernelGGL((outer_kernel<G, U, FLAT, PIER, false, SHADOW>), dim3(grid), dim3(kBlock), 0, stream, T.chunks, ROWS, A);
+    const dim3 g(static_cast<unsigned>(grid) * (kBlock / WG)), b(WG);
+    const unsigned lds = static_cast<unsigned>(shape.lds_bytes);
+    if (shape.nontemporal) hipLaunchKernelGGL((outer_kernel<WG, G, U, FLAT, PIER, true, SHADOW>), g, b, lds, stream, T.chunks, ROWS, A);
+    else hipLaunchKernelGGL((outer_kernel<WG, G, U, FLAT, PIER, false, SHADOW>), g, b, lds, stream, T.chunks, ROWS, A);
 }
 
-template <int G, int U, bool FLAT, bool PIER>
-static void outer_dispatch_nt(int grid, const OuterTables& T, const OuterArgs& A, bool nt, hipStream_t stream)
+template <int WG, int G, int U, bool FLAT, bool PIER>
+static void outer_dispatch_nt(int grid, const OuterTables& T, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
 {
     if constexpr (PIER) {
-        if (A.shadow) { outer_launch<G, U, FLAT, true, true>(grid, T, A, nt, stream); return; }
+        if (A.shadow) { outer_launch<WG, G, U, FLAT, true, true>(grid, T, A, shape, stream); return; }
     }
-    outer_launch<G, U, FLAT, PIER, false>(grid, T, A, nt, stream);
+    outer_launch<WG, G, U, FLAT, PIER, false>(grid, T, A, shape, stream);
 }
 
 template <int G, bool FLAT, bool PIER>
 static void outer_dispatch_u(int grid, const OuterTables& T, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
 {
-    const bool nt = shape.nontemporal != 0;
+    if (shape.wg_threads == 64) {   // one-wave workgroups: one vector per lane per stream only
+        outer_dispatch_nt<64, G, 1, FLAT, PIER>(grid, T, A, shape, stream);
+        return;
+    }
     // lanes keep (G + 2) * unroll 16-byte loads in flight; cap the product
     int u = shape.unroll;
     while (u > 1 && (G + 2) * u > 20) u >>= 1;
     switch (u) {
-    case 1: outer_dispatch_nt<G, 1, FLAT, PIER>(grid, T, A, nt, stream); break;
-    case 2: outer_dispatch_nt<G, 2, FLAT, PIER>(grid, T, A, nt, stream); break;
+    case 1: outer_dispatch_nt<kBlock, G, 1, FLAT, PIER>(grid, T, A, shape, stream); break;
+    case 2: outer_dispatch_nt<kBlock, G, 2, FLAT, PIER>(grid, T, A, shape, stream); break;
     default:
-        if constexpr ((G + 2) * 4 <= 20) outer_dispatch_nt<G, 4, FLAT, PIER>(grid, T, A, nt, stream);
-        else outer_dispatch_nt<G, 2, FLAT, PIER>(grid, T, A, nt, stream);
+        if constexpr ((G + 2) * 4 <= 20) outer_dispatch_nt<kBlock, G, 4, FLAT, PIER>(grid, T, A, shape, stream);
+        else outer_dispatch_nt<kBlock, G, 2, FLAT, PIER>(grid, T, A, shape, stream);
         break;
     }
 }
@@ -664,16 +712,18 @@ static void outer_dispatch_g(int grid, const OuterTables& T, const OuterArgs& A,
     case 4: outer_dispatch_u<4, FLAT, PIER>(grid, T, A, shape, stream); break;
     case 8: outer_dispatch_u<8, FLAT, PIER>(grid, T, A, shape, stream); break;
     default:
-        hipLaunchKernelGGL((outer_kernel_anyG<FLAT, PIER>), dim3(grid), dim3(kBlock), 0, stream, T.chunks, T.rows, A);
+        hipLaunchKernelGGL((outer_kernel_anyG<FLAT, PIER>), dim3(grid), dim3(kBlock),
+                           static_cast<unsigned>(shape.lds_bytes), stream, T.chunks, T.rows, A);
         break;
     }
 }
 
 hipError_t launch_outer(const Chunk* chunks, int n_chunks, const uint64_t* rows, int G,
                         float* flat_a, float* flat_M, int64_t flat_lo, float mu, float lr,
-                        bool pier_phase, bool shadow, const LaunchShape& shape, hipStream_t stream)
+                        bool pier_phase, bool shadow, const LaunchShape& requested, hipStream_t stream)
 {
     if (n_chunks <= 0) return hipSuccess;
+    const LaunchShape shape = resolved(requested, kOuterAutoLds);
     const OuterTables T{chunks, rows};
     OuterArgs A;
     A.flat_a = flat_a;

@@ -108,7 +108,12 @@ class Run:
 
         self.ctx = pier.pier_ctx_create(self.numels, G)
         if launch:
-            pier.pier_ctx_set_launch(self.ctx, **launch)
+            launch = dict(launch)
+            occupancy = {k: launch.pop(k) for k in ("wg_threads", "lds_bytes") if k in launch}
+            if launch:
+                pier.pier_ctx_set_launch(self.ctx, **launch)
+            if occupancy:
+                pier.pier_ctx_set_occupancy(self.ctx, **occupancy)
         for g in range(G):
             pier.pier_bind_replica(self.ctx, g, self.P[g].tensors, self.M1[g].tensors, self.V[g].tensors,
                                    self.Gd[g].tensors, grad_bf16)

@@ -98,6 +98,11 @@ def test_host_side_argument_errors():
     with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
         pier.pier_ctx_set_launch(ctx, unroll=3)
     pier.pier_ctx_set_launch(ctx, chunk_elems=4096, unroll=2, max_grid=16, nontemporal=0)
+    for bad in (dict(wg_threads=128), dict(wg_threads=32), dict(lds_bytes=65537), dict(lds_bytes=-2)):
+        with pytest.raises(pier.PierError):
+            pier.pier_ctx_set_occupancy(ctx, **bad)
+    pier.pier_ctx_set_occupancy(ctx, wg_threads=64, lds_bytes=13312)
+    pier.pier_ctx_set_occupancy(ctx)                    # back to each kernel's own choice
     with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):
         pier.pier_inner_adamw(ctx, 0, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, step=1)
     with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):

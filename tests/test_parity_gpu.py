@@ -74,6 +74,8 @@ def test_ragged_tensor_list_all_elements(G, pad):
     dict(chunk_elems=1024, unroll=1), dict(chunk_elems=1024, unroll=4),
     dict(chunk_elems=2048, unroll=2, nontemporal=0), dict(chunk_elems=65536, unroll=4, max_grid=3),
     dict(chunk_elems=16384, unroll=2, max_grid=7, nontemporal=0),
+    dict(wg_threads=256, lds_bytes=0), dict(wg_threads=64, lds_bytes=0), dict(wg_threads=64, lds_bytes=65536),
+    dict(wg_threads=256, lds_bytes=40960, unroll=2), dict(chunk_elems=4096, max_grid=5, wg_threads=64, lds_bytes=13312),
 ])
 def test_result_does_not_depend_on_launch_shape(launch):
     H_ = _harness()
@@ -127,7 +129,8 @@ def test_randomised_small_cases(case):
         numels.append(17)
     G = int(rng.choice([1, 2, 3, 4, 6, 7, 8, 9, 16]))
     launch = dict(chunk_elems=int(rng.choice([1024, 2048, 4096, 16384])), unroll=int(rng.choice([1, 2, 4])),
-                  max_grid=int(rng.choice([0, 0, 5, 64])), nontemporal=int(rng.choice([0, 1])))
+                  max_grid=int(rng.choice([0, 0, 5, 64])), nontemporal=int(rng.choice([0, 1])),
+                  wg_threads=int(rng.choice([0, 64, 256])), lds_bytes=int(rng.choice([-1, 0, 13312])))
     bf16 = bool(rng.integers(0, 2))
     pad = int(rng.integers(0, 2))
     shadow = bool(rng.integers(0, 2))
