@@ -4,8 +4,10 @@
 //
 //   hbm_stream_bench [elements-per-buffer, default 1557611200 (GPT-2 XL)]
 //
-// Every lane moves one 16-byte vector per stream with non-temporal accesses, one workgroup
-// per 256-vector tile (the launch shape the library uses).  Buffers are carved from one
+// Every lane moves one 16-byte vector per stream with non-temporal accesses.  Two launch
+// shapes: one four-wave workgroup per 256-vector tile with no limit on resident waves, and
+// one-wave workgroups with an unused LDS reservation that caps the waves resident per
+// compute unit (the shape the library launches with).  Buffers are carved from one
 // allocation at the stated spacing.  Prints GB/s (read + written bytes over kernel time).
 #include <hip/hip_runtime.h>
 #include <cstdio>
@@ -17,10 +19,10 @@ typedef float vfloat4 __attribute__((ext_vector_type(4)));
 
 struct Streams { float* r[10]; float* w[10]; };
 
-template <int NR, int NW>
-__global__ __launch_bounds__(256) void stream_kernel(Streams S, long n4, float c)
+template <int NR, int NW, int WG>
+__global__ __launch_bounds__(WG) void stream_kernel(Streams S, long n4, float c)
 {
-    const long i = static_cast<long>(blockIdx.x) * 256 + threadIdx.x;
+    const long i = static_cast<long>(blockIdx.x) * WG + threadIdx.x;
     if (i >= n4) return;
     vfloat4 acc = {c, c, c, c};
 #pragma unroll
@@ -31,27 +33,45 @@ __global__ __launch_bounds__(256) void stream_kernel(Streams S, long n4, float c
     if (NW == 0 && acc.x == 12345.678f) S.r[0][0] = acc.y;   // keeps the loads of a read-only pass alive
 }
 
-template <int NR, int NW>
-static void run(const char* what, const Streams& S, long n)
+// waves_per_cu = 0: four-wave workgroups, no cap; otherwise one-wave workgroups, each
+// reserving floor(160 KiB / waves_per_cu) of LDS (rounded down to 1 KiB) it never touches.
+template <int NR, int NW, int WG>
+static float time_kernel(const Streams& S, long n4, unsigned lds)
 {
-    const long n4 = n / 4;
-    const int grid = static_cast<int>((n4 + 255) / 256);
+    const int grid = static_cast<int>((n4 + WG - 1) / WG);
     hipEvent_t e0, e1;
     CK(hipEventCreate(&e0));
     CK(hipEventCreate(&e1));
-    hipLaunchKernelGGL((stream_kernel<NR, NW>), dim3(grid), dim3(256), 0, 0, S, n4, 1.0f);
+    hipLaunchKernelGGL((stream_kernel<NR, NW, WG>), dim3(grid), dim3(WG), lds, 0, S, n4, 1.0f);
+    CK(hipGetLastError());
     CK(hipEventRecord(e0, 0));
     const int iters = 5;
-    for (int k = 0; k < iters; ++k) hipLaunchKernelGGL((stream_kernel<NR, NW>), dim3(grid), dim3(256), 0, 0, S, n4, 1.0f);
+    for (int k = 0; k < iters; ++k) hipLaunchKernelGGL((stream_kernel<NR, NW, WG>), dim3(grid), dim3(WG), lds, 0, S, n4, 1.0f);
     CK(hipEventRecord(e1, 0));
     CK(hipEventSynchronize(e1));
     float ms = 0.f;
     CK(hipEventElapsedTime(&ms, e0, e1));
-    ms /= iters;
-    printf("%-64s %8.3f ms %6.0f GB/s\n", what, ms, static_cast<double>(NR + NW) * n * 4 / ms / 1e6);
-    fflush(stdout);
     CK(hipEventDestroy(e0));
     CK(hipEventDestroy(e1));
+    return ms / iters;
+}
+
+template <int NR, int NW>
+static void run(const char* what, const Streams& S, long n, int waves_per_cu = 0)
+{
+    const long n4 = n / 4;
+    char label[128];
+    float ms;
+    if (waves_per_cu > 0) {
+        const unsigned lds = (160u * 1024u / static_cast<unsigned>(waves_per_cu)) & ~1023u;
+        ms = time_kernel<NR, NW, 64>(S, n4, lds);
+        snprintf(label, sizeof label, "%s [1-wave WGs, %d per CU]", what, waves_per_cu);
+    } else {
+        ms = time_kernel<NR, NW, 256>(S, n4, 0);
+        snprintf(label, sizeof label, "%s", what);
+    }
+    printf("%-84s %8.3f ms %6.0f GB/s\n", label, ms, static_cast<double>(NR + NW) * n * 4 / ms / 1e6);
+    fflush(stdout);
 }
 
 int main(int argc, char** argv)
@@ -88,6 +108,8 @@ int main(int argc, char** argv)
         char what[96];
         snprintf(what, sizeof what, "AdamW pattern: 4 reads, 3 written back in place, %.0f GiB apart", d);
         run<4, 3>(what, S, n);
+        run<4, 3>(what, S, n, 12);
+        run<4, 3>(what, S, n, 8);
     }
     for (double d : {near, 8.0, 12.0, 16.0, 24.0}) {
         if (d < near || !fits(9 * d)) continue;
@@ -95,8 +117,12 @@ int main(int argc, char** argv)
         char what[96];
         snprintf(what, sizeof what, "outer pattern (G=8): 10 streams in place, %.0f GiB apart", d);
         run<10, 10>(what, S, n);
+        run<10, 10>(what, S, n, 8);
+        run<10, 10>(what, S, n, 4);
         snprintf(what, sizeof what, "lazy-start pattern: 10 reads, 2 written in place, %.0f GiB apart", d);
         run<10, 2>(what, S, n);
+        run<10, 2>(what, S, n, 8);
+        run<10, 2>(what, S, n, 6);
     }
     CK(hipFree(arena));
     return 0;

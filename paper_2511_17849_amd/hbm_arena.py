@@ -31,13 +31,15 @@ class HbmArena:
 
     def alloc(self, numel, dtype=torch.float32, cls=None):
         """A flat tensor of ``numel`` elements on whole granules of class ``cls`` (contiguous
-        run, first fit).  cls=None, or no run left in that class: the class with most free room
-        that still has a run; raises if nothing fits."""
+        run, first fit); ``cls`` may also be a list of classes in order of preference.
+        cls=None, or no run left in any preferred class: the class with most free room that
+        still has a run; raises if nothing fits."""
         esize = torch.empty(0, dtype=dtype).element_size()
         need = max(1, -(-numel * esize // self.granule))
         order = []
-        if cls is not None:
-            order.append(cls % self.n_classes)
+        for c in ([] if cls is None else cls if isinstance(cls, (list, tuple)) else [cls]):
+            if c % self.n_classes not in order:
+                order.append(c % self.n_classes)
         sizes = self.class_sizes()
         order += [c for c in sorted(range(self.n_classes), key=lambda c: -sizes[c]) if c not in order]
         for c in order:

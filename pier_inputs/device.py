@@ -77,18 +77,24 @@ def init_params(flat_list, w):
 class PlacedState:
     """All buffers of one workload - theta, m, v, gradient per replica, anchor and M -
     as FlatLists.  With ``arena`` (a paper_2511_17849_amd.HbmArena) the buffers are carved
-    out of it by address class.  policy "pairs" (default; the fastest measured for the AdamW
-    launch, 6.40-6.49 TB/s in a 4-stream microbenchmark against 6.33-6.39 for "spread"):
-    theta_g and m_g in class g, v_g and grad_g in class g + 1.  policy "spread": class(theta_g)
-    = g, class(m_g) = g + 1, class(v_g) = g + 2, class(grad_g) = g.  All modulo the number of
-    classes; either way the theta of different replicas rotate over the classes, and anchor and
-    M go to the classes that hold the fewest theta buffers, which is what the outer step wants.
-    Without an arena the buffers are separate allocations made kind by kind.
+    out of it by address class.  Measured on MI355X at GPT-2 XL size: a launch streams fastest
+    when its buffers lie in exactly two classes, half in each - for the AdamW launch theta_g, m_g
+    in one class and v_g, grad_g in another (6.40-6.55 TB/s against 6.33-6.39 with one buffer per
+    class and 5.6-6.1 with all four in one), for the outer step the G thetas, the anchor and M
+    split five and five over two classes (6.47-6.54 TB/s against 6.35-6.42 over three classes).
+      policy "two_class" (default): theta_g and m_g, back to back, in class g mod 2; the anchor and
+        M in whichever of classes 0 and 1 then holds fewer of the outer step's buffers; v_g and
+        grad_g, back to back, in class 2 while it has room, else in class 1 - (g mod 2).
+      policy "pairs": theta_g, m_g in class g mod 3, v_g, grad_g in class (g + 1) mod 3, anchor
+        and M where the fewest thetas are (the outer step's buffers then span three classes).
+      policy "spread": class(theta_g) = g, class(m_g) = g + 1, class(v_g) = g + 2, class(grad_g) = g.
+    With fewer classes than a policy names, classes are taken modulo their number.  Without an
+    arena the buffers are separate allocations made kind by kind.
     outer="device" | "pinned" | None places anchor and M on the device, in pinned host
     memory (flat arrays for the offload path), or nowhere."""
 
     def __init__(self, numels, G, grad_dtype=torch.float32, arena=None, outer="device", shared_grad=False,
-                 policy="pairs"):
+                 policy="two_class"):
         self.numels = list(numels)
         N = sum(self.numels)
         ncls = arena.n_classes if arena is not None else 1
@@ -108,30 +114,51 @@ class PlacedState:
             fl.tensors = [fl.flat[s:s + n] for s, n in zip(fl.starts, fl.numels)]
             return fl
 
-        if policy == "pairs":
-            kp, km, kv, kg = 0, 0, 1, 1
-        else:  # "spread"
-            kp, km, kv, kg = 0, 1, 2, 0
-        self.P, self.M1, self.V = [], [], []
-        for g in range(G):          # theta_g and m_g allocated back to back
-            self.P.append(make(torch.float32, g + kp))
-            self.M1.append(make(torch.float32, g + km))
-        for g in range(G):
-            self.V.append(make(torch.float32, g + kv))
-        if outer == "device":
-            load = [sum(1 for g in range(G) if g % ncls == c) for c in range(ncls)]
-            ca = load.index(min(load))
-            load[ca] += 1
-            cm = load.index(min(load))
-            self.A, self.Mo = make(torch.float32, ca), make(torch.float32, cm)
-        elif outer == "pinned":
-            self.A = FlatList(self.numels, pinned=True, zero=False)
-            self.Mo = FlatList(self.numels, pinned=True, zero=False)
+        def make_outer(classes_of_theta, candidates):
+            if outer == "device":
+                load = {c: sum(1 for x in classes_of_theta if x == c) for c in candidates}
+                ca = min(candidates, key=lambda c: load[c])
+                load[ca] += 1
+                cm = min(candidates, key=lambda c: load[c])
+                self.A, self.Mo = make(torch.float32, ca), make(torch.float32, cm)
+            elif outer == "pinned":
+                self.A = FlatList(self.numels, pinned=True, zero=False)
+                self.Mo = FlatList(self.numels, pinned=True, zero=False)
+            else:
+                self.A = self.Mo = None
+
+        self.P, self.M1, self.V, self.Gd = [], [], [], []
+        if policy == "two_class":
+            two = min(2, ncls)
+            for g in range(G):          # theta_g and m_g allocated back to back
+                self.P.append(make(torch.float32, g % two))
+                self.M1.append(make(torch.float32, g % two))
+            make_outer([g % two for g in range(G)], list(range(two)))
+            shared = None
+            for g in range(G):          # v_g and grad_g back to back, away from theta_g's class
+                away = [2, 1 - g % 2] if ncls >= 3 else [1 - g % 2]
+                self.V.append(make(torch.float32, away))
+                if shared_grad:
+                    shared = shared or make(grad_dtype, away)
+                    self.Gd.append(shared)
+                else:
+                    self.Gd.append(make(grad_dtype, away))
         else:
-            self.A = self.Mo = None
-        if shared_grad:
-            self.Gd = [make(grad_dtype, kg)] * G
-        else:
-            self.Gd = [make(grad_dtype, g + kg) for g in range(G)]
+            if policy == "pairs":
+                kp, km, kv, kg = 0, 0, 1, 1
+            elif policy == "spread":
+                kp, km, kv, kg = 0, 1, 2, 0
+            else:
+                raise ValueError("unknown placement policy %r" % (policy,))
+            for g in range(G):
+                self.P.append(make(torch.float32, g + kp))
+                self.M1.append(make(torch.float32, g + km))
+            for g in range(G):
+                self.V.append(make(torch.float32, g + kv))
+            make_outer([g % ncls for g in range(G)], list(range(ncls)))
+            if shared_grad:
+                self.Gd = [make(grad_dtype, kg)] * G
+            else:
+                self.Gd = [make(grad_dtype, g + kg) for g in range(G)]
         for fl in self.M1 + self.V + ([self.Mo] if self.Mo is not None else []):
             fl.flat.zero_()

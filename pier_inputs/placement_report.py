@@ -1,10 +1,10 @@
 """Placement diagnostic: how fast the two optimizer kernels stream at one workload's size under
 different placements of its buffers in HBM.
 
-    python -m pier_inputs.placement_report [--workload gpt2_xl] [--policies plain pairs spread]
+    python -m pier_inputs.placement_report [--workload gpt2_xl] [--policies plain two_class pairs spread]
 
-"plain" allocates every buffer separately, kind by kind; "pairs" and "spread" carve them out of
-an arena classified by pier_hbm_probe (see PlacedState for the two policies).  Each policy runs in
+"plain" allocates every buffer separately, kind by kind; the others carve them out of an arena
+classified by pier_hbm_probe (see PlacedState for the policies).  Each policy runs in
 the same process on freshly allocated state; prints one line per policy with the AdamW rate of
 every replica and the outer-step rates.  No optimizer arithmetic here: it only times launches.
 """
@@ -33,7 +33,7 @@ def measure(w, policy, iters):
         arena = pier.HbmArena(free - (8 << 30))
         info["probe_s"] = round(time.time() - t0, 2)
         info["classes"] = "".join(str(c) for c in arena.classes)
-    S = dev.PlacedState(w.numels, G, grad_dtype=gdt, arena=arena, policy=policy if arena else "pairs")
+    S = dev.PlacedState(w.numels, G, grad_dtype=gdt, arena=arena, policy=policy if arena else "two_class")
     for g in range(G):
         dev.fill_normal(S.P[g].flat, seed=w.seed, stream=shapes.PARAM_STREAM, step=0, std=w.param_std)
         dev.fill_normal(S.Gd[g].flat, seed=w.seed, stream=g, step=1, std=w.grad_std)
@@ -79,7 +79,7 @@ def measure(w, policy, iters):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="gpt2_xl")
-    ap.add_argument("--policies", nargs="+", default=["plain", "pairs", "spread"])
+    ap.add_argument("--policies", nargs="+", default=["plain", "two_class", "pairs", "spread"])
     ap.add_argument("--iters", type=int, default=5)
     args = ap.parse_args()
     w = shapes.workloads()[args.workload]

@@ -38,27 +38,58 @@ def test_alloc_respects_classes_and_contiguity():
     assert all(e0 <= b1 for (_, e0), (b1, _) in zip(spans, spans[1:]))
 
 
-def test_placement_policy_on_a_linear_three_class_arena():
-    """The policy PlacedState applies: theta_g and m_g share a class, v_g and grad_g the next one,
-    the thetas rotate over the classes, anchor and M go where the fewest thetas are."""
+def _placed(policy, G=8, classes=None, **kw):
     from pier_inputs import device as dev
     g = 4096                                             # granule bytes; one buffer = 3 granules
-    a = fake_arena([0] * 48 + [1] * 48 + [2] * 44, granule=g)
-    calls = []
-    real_alloc = a.alloc
-
-    def spy(numel, dtype=torch.float32, cls=None):
-        t, c = real_alloc(numel, dtype, cls)
-        calls.append(c)
-        return t, c
-    a.alloc = spy
+    a = fake_arena(classes or [0] * 48 + [1] * 48 + [2] * 44, granule=g)
     n = 3 * g // 4 - 8
-
-    class S(dev.PlacedState):
-        pass
     # PlacedState zeroes its buffers with torch ops, which is fine on the CPU tensors of the fake arena
-    s = S([n], 8, arena=a)
-    P, M, V, Gd = [x.cls for x in s.P], [x.cls for x in s.M1], [x.cls for x in s.V], [x.cls for x in s.Gd]
+    s = dev.PlacedState([n], G, arena=a, policy=policy, **kw)
+    cls = lambda xs: [x.cls for x in xs]
+    return s, cls(s.P), cls(s.M1), cls(s.V), cls(s.Gd), a
+
+
+def _no_overlap(s):
+    bufs = {id(x.flat): x.flat for x in s.P + s.M1 + s.V + s.Gd + [s.A, s.Mo]}.values()
+    spans = sorted((x.data_ptr(), x.data_ptr() + x.numel() * x.element_size()) for x in bufs)
+    assert all(e0 <= b1 for (_, e0), (b1, _) in zip(spans, spans[1:]))
+
+
+def test_default_policy_keeps_every_launch_in_two_classes():
+    """theta_g, m_g in class g mod 2; the outer step's ten buffers five and five in classes 0 and
+    1; v_g, grad_g in class 2 until it is full (14 buffers of 3 granules in 44), then in the class
+    theta_g is not in."""
+    s, P, M, V, Gd, a = _placed("two_class")
+    assert P == [0, 1, 0, 1, 0, 1, 0, 1] and M == P
+    assert sorted([s.A.cls, s.Mo.cls]) == [0, 1]
+    assert V == [2] * 7 + [0] and Gd == V
+    for g in range(8):          # back to back: m_g follows theta_g, grad_g follows v_g
+        assert s.M1[g].flat.data_ptr() - s.P[g].flat.data_ptr() == 3 * a.granule
+        assert s.Gd[g].flat.data_ptr() - s.V[g].flat.data_ptr() == 3 * a.granule
+    _no_overlap(s)
+    # odd group count: anchor and M even the two classes out
+    s, P, M, V, Gd, _ = _placed("two_class", G=3)
+    assert P == [0, 1, 0] and [s.A.cls, s.Mo.cls] == [1, 0] and V == [2, 2, 2]
+    # one shared gradient buffer
+    s, P, M, V, Gd, _ = _placed("two_class", G=4, shared_grad=True)
+    assert len({id(x) for x in s.Gd}) == 1 and Gd == [2] * 4
+    # two classes only, and a single one
+    s, P, M, V, Gd, _ = _placed("two_class", G=4, classes=[0] * 40 + [1] * 40)
+    assert P == [0, 1, 0, 1] and V == [1, 0, 1, 0] and Gd == V
+    s, P, M, V, Gd, _ = _placed("two_class", G=2, classes=[0] * 40)
+    assert P + M + V + Gd == [0] * 8
+    _no_overlap(s)
+    with pytest.raises(ValueError):
+        _placed("nonsense")
+
+
+def test_pairs_and_spread_policies_on_a_linear_three_class_arena():
+    """"pairs": theta_g and m_g share a class, v_g and grad_g the next one, the thetas rotate over
+    the classes, anchor and M go where the fewest thetas are."""
+    s, P, M, V, Gd, _ = _placed("pairs")
     assert P == [0, 1, 2, 0, 1, 2, 0, 1] and M == P
     assert V == [1, 2, 0, 1, 2, 0, 1, 2] and Gd == V
     assert s.A.cls == 2 and s.Mo.cls in (0, 1)           # class 2 holds two thetas, the others three
+    _no_overlap(s)
+    s, P, M, V, Gd, _ = _placed("spread", G=3)
+    assert P == [0, 1, 2] and M == [1, 2, 0] and V == [2, 0, 1] and Gd == P
