@@ -27,7 +27,7 @@ HBM_PEAK_GBPS = 8000.0        # MI355X published HBM3E peak
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the
 # same counters' reading of a plain copy kernel); summary in
 # profiles/kernels_gpt2_xl_hbm_traffic_pmc.md.  Only valid for the workload it was taken on.
-MEASURED_TRAFFIC_GB = {"gpt2_xl": {"adamw": 43.808, "outer": 124.824}}
+MEASURED_TRAFFIC_GB = {"gpt2_xl": {"adamw": 44.003, "outer": 125.005}}
 
 
 def parse():
