@@ -143,13 +143,17 @@ def main():
     # offload stream as their outer step; the PCIe time is then part of the step and `value`
     # is flagged as PCIe-inclusive in config
     host_outer = w.offload
-    S = dev.PlacedState(w.numels, G, grad_dtype=gdt, arena=arena, outer="pinned" if host_outer else "device")
+    # the 7B configuration keeps one gradient buffer for all replicas (each launch reads it whole,
+    # so the traffic is the same): nine of its 26 GiB buffers fit the three address classes, and
+    # only with a single gradient buffer do every replica's four streams lie in two classes
+    S = dev.PlacedState(w.numels, G, grad_dtype=gdt, arena=arena, outer="pinned" if host_outer else "device",
+                        shared_grad=host_outer)
     P, M1, V, Gd, A, Mo = S.P, S.M1, S.V, S.Gd, S.A, S.Mo
     with torch.cuda.stream(stream):
         dev.init_params(P[0], w)
         for g in range(1, G):
             P[g].flat.copy_(P[0].flat)
-        for g in range(G):
+        for g in range(1 if host_outer else G):
             Gd[g].fill_normal(seed=w.seed, stream=g, step=1, std=w.grad_std, hip_stream=stream)
     stream.synchronize()
     A.flat.copy_(P[0].flat)
