@@ -133,7 +133,8 @@ pier_status allocate_tables(pier_ctx* c)
 {
     c->h_chunks.clear();
     build_chunks(c, 0, c->N, c->h_chunks);
-    if (c->h_chunks.size() > static_cast<size_t>(INT32_MAX))
+    // a launch has up to four workgroups per chunk and the grid must fit 31 bits
+    if (c->h_chunks.size() > static_cast<size_t>(INT32_MAX / 4))
         return fail(PIER_ERR_INVALID_ARG, "too many chunks; raise chunk_elems");
     c->n_chunks = static_cast<int>(c->h_chunks.size());
     if (c->n_chunks > 0) {
