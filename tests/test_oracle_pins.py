@@ -22,6 +22,59 @@ def tol(ref):
     return 1e-6 * np.maximum(1.0, np.abs(ref))
 
 
+# ---------------------------------------------------------------- exact symmetries
+#
+# IEEE arithmetic rounds symmetrically in sign and is exact under scaling by a power of two
+# (away from overflow and subnormals), so some symmetries of the update rules must hold bit for
+# bit, whatever the operation order: a wrong sign, a term that does not scale, a constant added
+# where a product belongs breaks them.
+
+def test_adamw_is_odd_in_theta_m_g_bit_for_bit():
+    rng = np.random.default_rng(21)
+    n = 4096
+    p0, m0 = f32(rng.normal(0, 0.02, n)), f32(rng.normal(0, 1e-3, n))
+    v0, g0 = f32(rng.uniform(0, 1e-6, n)), f32(rng.normal(0, 1e-3, n))
+    a = [p0.copy(), m0.copy(), v0.copy()]
+    b = [-p0, -m0, v0.copy()]
+    for step in (1, 2, 7):
+        O.adamw(*a, g0, step=step, **HP)
+        O.adamw(*b, f32(-g0), step=step, **HP)
+        assert np.array_equal(a[0], -b[0]) and np.array_equal(a[1], -b[1]) and np.array_equal(a[2], b[2])
+    assert not np.array_equal(a[0], p0)
+
+
+def test_outer_is_odd_and_scales_by_powers_of_two_bit_for_bit():
+    rng = np.random.default_rng(22)
+    n, G = 2048, 4
+    a0, M0 = f32(rng.normal(0, 0.02, n)), f32(rng.normal(0, 1e-3, n))
+    th0 = [f32(a0 + rng.normal(0, 1e-3, n)) for _ in range(G)]
+    for phase in (1, 0):
+        ref = [t.copy() for t in th0], a0.copy(), M0.copy()
+        O.outer(*ref, mu=0.95, lr=1.1, phase=phase)
+        for scale in (-1.0, 4.0, -0.125):
+            sc = [f32(scale * t) for t in th0], f32(scale * a0), f32(scale * M0)
+            O.outer(*sc, mu=0.95, lr=1.1, phase=phase)
+            assert np.array_equal(sc[1], f32(scale * ref[1])) and np.array_equal(sc[2], f32(scale * ref[2]))
+            for g in range(G):
+                assert np.array_equal(sc[0][g], f32(scale * ref[0][g]))
+    # and the order of the groups matters only through rounding: a permutation stays within tolerance
+    ref = [t.copy() for t in th0], a0.copy(), M0.copy()
+    O.outer(*ref, mu=0.95, lr=1.1, phase=1)
+    perm = [th0[2].copy(), th0[0].copy(), th0[3].copy(), th0[1].copy()], a0.copy(), M0.copy()
+    O.outer(*perm, mu=0.95, lr=1.1, phase=1)
+    assert np.all(np.abs(perm[1] - ref[1]) <= tol(ref[1]))
+
+
+def test_clip_coefficient_scales_inversely_with_the_gradient():
+    rng = np.random.default_rng(23)
+    g = f32(rng.normal(0, 1e-2, 10_000))
+    s1, s4 = O.sumsq(g), O.sumsq(f32(4.0 * g))
+    assert s4 == 16.0 * s1                                   # exact: every term scales by 2^4
+    c1, c4 = O.clip_coef(s1, 0.5), O.clip_coef(s4, 0.5)
+    assert c1 < 1.0 and abs(c4 * 4.0 / c1 - 1.0) < 2e-6      # the 1e-6 in the denominator is not scaled
+    assert O.clip_coef(s1, 1e3) == 1.0
+
+
 # ---------------------------------------------------------------- inner AdamW
 
 def test_adamw_first_step_closed_form_hand_case():
