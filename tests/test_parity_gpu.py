@@ -439,6 +439,72 @@ def test_plain_c_client_of_the_abi(tmp_path):
         assert np.array_equal(g_, w_), k           # and in fact bit for bit
 
 
+def _same_bits_or_both_nan(got, want):
+    got, want = np.asarray(got), np.asarray(want)
+    both_nan = np.isnan(got) & np.isnan(want)
+    return both_nan | (got.view(np.uint32) == want.view(np.uint32))
+
+
+def test_special_values_take_the_same_path_as_the_oracle():
+    """Zeros of both signs, subnormals, the smallest and largest normals, infinities and NaN in
+    every input: the kernels use IEEE division and square root with subnormals kept, so the
+    result is the oracle's bit for bit (any NaN standing for any other NaN)."""
+    import paper_2511_17849_amd as pier
+    from oracle import pier_oracle as O
+    tiny, big = np.float32(1.1754944e-38), np.float32(3.4028235e38)
+    vals = np.array([0.0, -0.0, 1e-45, -1e-45, 3e-41, tiny, -tiny, 1e-30, 1e-20, -1e-12, 1e-3, -0.02, 1.0,
+                     1e10, -1e19, 1e30, big, -big, np.inf, -np.inf, np.nan], dtype=np.float32)
+    nonneg = np.array([0.0, 1e-45, 3e-41, tiny, 1e-30, 1e-12, 1e-6, 1.0, 1e19, big, np.inf, np.nan], dtype=np.float32)
+    rng = np.random.default_rng(77)
+    n = 1024 * 5 + 3                          # vector path, ragged tile and scalar tail
+    pick = lambda pool: np.ascontiguousarray(rng.choice(pool, n))
+    p, m, v, g = pick(vals), pick(vals), pick(nonneg), pick(vals)
+    hp = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    dp, dm, dv, dg = (torch.from_numpy(x.copy()).cuda() for x in (p, m, v, g))
+    ctx = pier.pier_ctx_create([n], 2)
+    th1 = torch.from_numpy(pick(vals)).cuda()
+    pier.pier_bind_replica(ctx, 0, [dp], [dm], [dv], [dg])
+    pier.pier_bind_replica(ctx, 1, [th1], [dm], [dv], [dg])
+    with np.errstate(all="ignore"):
+        for step in (1, 3):
+            pier.pier_inner_adamw(ctx, 0, step=step, **hp)
+            O.adamw(p, m, v, g, step=step, **hp)
+            torch.cuda.synchronize()
+            for name, d, h in (("theta", dp, p), ("m", dm, m), ("v", dv, v)):
+                ok = _same_bits_or_both_nan(d.cpu().numpy(), h)
+                assert ok.all(), (name, step, int((~ok).sum()), d.cpu().numpy()[~ok][:4], h[~ok][:4])
+        # outer step, both phases, on the same menagerie
+        a, M = pick(vals), pick(vals)
+        da, dM = torch.from_numpy(a.copy()).cuda(), torch.from_numpy(M.copy()).cuda()
+        pier.pier_bind_outer(ctx, pier.PIER_LOC_DEVICE, [da], [dM])
+        th = [p, th1.cpu().numpy().copy()]
+        for phase in (WARMUP, PIER):
+            pier.pier_outer_step(ctx, outer_lr=1.1, mu=0.95, phase=phase)
+            O.outer(th, a, M, mu=0.95, lr=1.1, phase=phase)
+            torch.cuda.synchronize()
+            for name, d, h in (("anchor", da, a), ("M", dM, M), ("theta0", dp, th[0]), ("theta1", th1, th[1])):
+                ok = _same_bits_or_both_nan(d.cpu().numpy(), h)
+                assert ok.all(), (name, phase, int((~ok).sum()), d.cpu().numpy()[~ok][:4], h[~ok][:4])
+        # clipping with a non-finite norm: an infinite gradient gives coefficient 0 (and 0 * inf = NaN
+        # for that element), a NaN gradient leaves the coefficient at 1; same on both sides
+        for bad in (np.inf, np.nan):
+            g2 = np.ascontiguousarray(rng.normal(0, 1e-3, n).astype(np.float32))
+            g2[n // 2] = bad
+            dg.copy_(torch.from_numpy(g2))
+            p2, m2, v2 = (x.cpu().numpy().copy() for x in (dp, dm, dv))
+            pier.pier_inner_adamw_clipped(ctx, 0, step=4, max_norm=1.0, **hp)
+            torch.cuda.synchronize()
+            coef = O.clip_coef(O.sumsq(g2), 1.0)
+            norm_d, coef_d = pier.pier_grad_norm_last(ctx, 0)
+            assert coef_d == coef == (0.0 if bad == np.inf else 1.0)
+            assert (np.isinf(norm_d) if bad == np.inf else np.isnan(norm_d))
+            O.adamw(p2, m2, v2, g2, step=4, grad_scale=coef, **hp)
+            for name, d, h in (("theta", dp, p2), ("m", dm, m2), ("v", dv, v2)):
+                ok = _same_bits_or_both_nan(d.cpu().numpy(), h)
+                assert ok.all(), (name, bad, int((~ok).sum()))
+    pier.pier_ctx_destroy(ctx)
+
+
 def test_all_empty_model_is_a_no_op():
     import paper_2511_17849_amd as pier
     ctx = pier.pier_ctx_create([0, 0], 1)
