@@ -201,12 +201,37 @@ pier_status pier_offload_stream(pier_ctx* ctx, const pier_outer_hp* hp, size_t c
  * n_granules consecutive granules of granule_bytes (multiple of 2 MiB, >= 512 MiB)
  * that start at the device pointer `arena`, by timing a two-buffer in-place streaming
  * pass between granules: class_out[g] (host array) receives a small class id, equal for
- * granules that behave as one class.  A caller then places buffers that one launch
- * touches together (theta_g, m_g, v_g; the theta of different replicas, anchor, M) in
- * different classes.  Synchronous (a second or two); OVERWRITES the arena's contents;
+ * granules that behave as one class.  A caller then places the buffers that one launch
+ * touches together as pier_placement_plan says.  Synchronous (a few seconds); OVERWRITES
+ * the arena's contents;
  * enqueues on hip_stream and waits for it. */
 pier_status pier_hbm_probe(void* arena, size_t bytes, size_t granule_bytes, int32_t* class_out,
                            int n_granules, void* hip_stream);
+
+/* The placement that goes with the probe (again no operation of the paper; host
+ * arithmetic only, touches no GPU).  Measured on MI355X: a launch streams fastest when
+ * its buffers lie in exactly two classes, half in each.  For a model with n_replicas
+ * replicas this returns the class of every model-sized buffer:
+ *   theta_g and m_g           class g mod 2;
+ *   anchor, momentum          (outer_on_device != 0) whichever of classes 0 and 1 then holds
+ *                             fewer of the outer step's n_replicas + 2 buffers;
+ *   v_g and grad_g            class 2 while the pair fits there, else the class of {0, 1}
+ *                             that theta_g is not in (shared_grad != 0: one gradient
+ *                             buffer for all replicas, placed with replica 0's v).
+ * room[c] (host array of n_classes entries) is the number of buffers of this model that
+ * class c still holds; a full class passes its buffer on to the next class on its list,
+ * then to the class with most room.  With one or two classes the same rules apply modulo
+ * the class count.  The caller should allocate in the order the plan was made - theta_0,
+ * m_0, theta_1, m_1, ..., anchor, momentum, v_0, grad_0, v_1, ... - so that buffers that
+ * are streamed together also end up next to each other inside a class.
+ * replicas: host array of n_replicas entries (out); anchor_class, momentum_class: out,
+ * -1 when outer_on_device == 0.  PIER_ERR_OOM when the buffers do not fit room[]. */
+typedef struct {
+    int32_t theta, m, v, grad;
+} pier_replica_placement;
+pier_status pier_placement_plan(int n_classes, const int64_t* room, int n_replicas, int shared_grad,
+                                int outer_on_device, pier_replica_placement* replicas,
+                                int32_t* anchor_class, int32_t* momentum_class);
 
 /* ------------------------------------------------------------- schedules
  * Pure host helpers; t = iteration (1-based), T = total iterations (> 0). */

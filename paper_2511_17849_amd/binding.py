@@ -80,6 +80,8 @@ def _load():
         "pier_ctx_numel": (i64, [vp]),
         "pier_ctx_set_launch": (i32, [vp, i64, i32, i32, i32]),
         "pier_ctx_set_occupancy": (i32, [vp, i32, i32]),
+        "pier_placement_plan": (i32, [i32, ctypes.POINTER(i64), i32, i32, i32, vp,
+                                      ctypes.POINTER(i32), ctypes.POINTER(i32)]),
         "pier_bind_replica": (i32, [vp, i32, pp, pp, pp, pp, i32]),
         "pier_bind_shadow": (i32, [vp, i32, pp]),
         "pier_bind_outer": (i32, [vp, i32, pp, pp]),
@@ -245,6 +247,22 @@ def pier_offload_stream(ctx, *, outer_lr, mu, phase, chunk_bytes, workspace, com
                                        int(wbytes), _stream(compute_stream), _stream(h2d_stream),
                                        _stream(d2h_stream), ctypes.byref(stats) if want_stats else None))
     return stats
+
+
+def pier_placement_plan(room, n_replicas, shared_grad=False, outer_on_device=True):
+    """Address class of every model-sized buffer.  ``room[c]``: buffers class c still holds.
+    Returns (replicas, anchor_class, momentum_class), replicas a list of dicts with the keys
+    theta, m, v, grad; the two classes are -1 when the outer state is not on the device."""
+    room = [int(r) for r in room]
+    arr = (ctypes.c_int64 * len(room))(*room)
+    rep = (ctypes.c_int32 * (4 * int(n_replicas)))()
+    a, m = ctypes.c_int32(), ctypes.c_int32()
+    _check(_load().pier_placement_plan(len(room), arr, int(n_replicas), int(bool(shared_grad)),
+                                       int(bool(outer_on_device)), ctypes.cast(rep, ctypes.c_void_p),
+                                       ctypes.byref(a), ctypes.byref(m)))
+    reps = [dict(theta=rep[4 * g], m=rep[4 * g + 1], v=rep[4 * g + 2], grad=rep[4 * g + 3])
+            for g in range(int(n_replicas))]
+    return reps, a.value, m.value
 
 
 def pier_hbm_probe(arena, granule_bytes, stream=None):

@@ -789,6 +789,84 @@ pier_status pier_hbm_probe(void* arena, size_t bytes, size_t granule_bytes, int3
     return PIER_OK;
 }
 
+pier_status pier_placement_plan(int n_classes, const int64_t* room_in, int n_replicas, int shared_grad,
+                                int outer_on_device, pier_replica_placement* replicas,
+                                int32_t* anchor_class, int32_t* momentum_class)
+{
+    if (n_classes < 1 || n_classes > 64) return fail(PIER_ERR_INVALID_ARG, "n_classes = %d, need 1..64", n_classes);
+    if (!room_in || !replicas || !anchor_class || !momentum_class)
+        return fail(PIER_ERR_INVALID_ARG, "a pointer is NULL");
+    if (n_replicas < 1 || n_replicas > PIER_MAX_REPLICAS)
+        return fail(PIER_ERR_INVALID_ARG, "n_replicas = %d, need 1..%d", n_replicas, PIER_MAX_REPLICAS);
+    std::vector<int64_t> room(room_in, room_in + n_classes);
+    for (int c = 0; c < n_classes; ++c)
+        if (room[c] < 0) return fail(PIER_ERR_INVALID_ARG, "room[%d] is negative", c);
+    const int two = std::min(2, n_classes);
+
+    // takes `count` buffers from the first class of prefs[0..n_prefs) that holds them all, else
+    // from the class with most room; -1 if no class holds them
+    auto take = [&](const int* prefs, int n_prefs, int count) -> int {
+        for (int i = 0; i < n_prefs; ++i)
+            if (room[prefs[i]] >= count) {
+                room[prefs[i]] -= count;
+                return prefs[i];
+            }
+        int best = 0;
+        for (int c = 1; c < n_classes; ++c)
+            if (room[c] > room[best]) best = c;
+        if (room[best] < count) return -1;
+        room[best] -= count;
+        return best;
+    };
+    auto full = [&]() { return fail(PIER_ERR_OOM, "the model's buffers do not fit the room given"); };
+
+    std::vector<int> outer_load(n_classes, 0);
+    for (int g = 0; g < n_replicas; ++g) {
+        const int want[2] = {g % two, (g + 1) % two};
+        int c = take(want, two, 2);                 // theta_g and m_g together
+        if (c >= 0) {
+            replicas[g].theta = replicas[g].m = c;
+        } else {
+            if ((replicas[g].theta = take(want, two, 1)) < 0) return full();
+            if ((replicas[g].m = take(want, two, 1)) < 0) return full();
+        }
+        ++outer_load[replicas[g].theta];
+    }
+    *anchor_class = *momentum_class = -1;
+    if (outer_on_device) {
+        for (int32_t* out : {anchor_class, momentum_class}) {
+            int lo = 0;
+            for (int c = 1; c < two; ++c)
+                if (outer_load[c] < outer_load[lo]) lo = c;
+            const int want[2] = {lo, (lo + 1) % two};
+            if ((*out = take(want, two, 1)) < 0) return full();
+            ++outer_load[*out];
+        }
+    }
+    int shared = -1;
+    for (int g = 0; g < n_replicas; ++g) {
+        // away from theta_g's class: class 2 first, then the other one of classes 0 and 1
+        const int th = replicas[g].theta;
+        int want[2];
+        int n_want = 0;
+        if (n_classes >= 3 && th != 2) want[n_want++] = 2;
+        if (n_classes >= 2) want[n_want++] = th == 0 ? 1 : 0;
+        if (n_want == 0) want[n_want++] = 0;
+        const bool need_grad = !shared_grad || shared < 0;
+        int c = take(want, n_want, need_grad ? 2 : 1);   // v_g and grad_g together
+        if (c >= 0) {
+            replicas[g].v = c;
+            replicas[g].grad = need_grad ? c : shared;
+        } else {
+            if ((replicas[g].v = take(want, n_want, 1)) < 0) return full();
+            replicas[g].grad = shared;
+            if (need_grad && (replicas[g].grad = take(want, n_want, 1)) < 0) return full();
+        }
+        if (shared_grad && shared < 0) shared = replicas[g].grad;
+    }
+    return PIER_OK;
+}
+
 float pier_mu_schedule(int64_t t, int64_t T)
 {
     if (10 * t >= T && 100 * t < 15 * T) return 0.99f;

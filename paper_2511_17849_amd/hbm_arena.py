@@ -29,6 +29,21 @@ class HbmArena:
                 out[c] += self.granule
         return out
 
+    def room(self, numel, dtype=torch.float32):
+        """How many more buffers of ``numel`` elements each class holds (disjoint runs of free
+        granules, counted first fit): the ``room`` argument of pier_placement_plan."""
+        esize = torch.empty(0, dtype=dtype).element_size()
+        need = max(1, -(-numel * esize // self.granule))
+        out = [0] * self.n_classes
+        run, prev = 0, None
+        for c, u in zip(self.classes, self.used):
+            run = run + 1 if (not u and c == prev) else (0 if u else 1)
+            prev = None if u else c
+            if run == need:
+                out[c] += 1
+                run = 0
+        return out
+
     def alloc(self, numel, dtype=torch.float32, cls=None):
         """A flat tensor of ``numel`` elements on whole granules of class ``cls`` (contiguous
         run, first fit); ``cls`` may also be a list of classes in order of preference.

@@ -82,9 +82,10 @@ class PlacedState:
     in one class and v_g, grad_g in another (6.40-6.55 TB/s against 6.33-6.39 with one buffer per
     class and 5.6-6.1 with all four in one), for the outer step the G thetas, the anchor and M
     split five and five over two classes (6.47-6.54 TB/s against 6.35-6.42 over three classes).
-      policy "two_class" (default): theta_g and m_g, back to back, in class g mod 2; the anchor and
-        M in whichever of classes 0 and 1 then holds fewer of the outer step's buffers; v_g and
-        grad_g, back to back, in class 2 while it has room, else in class 1 - (g mod 2).
+      policy "two_class" (default): the library's pier_placement_plan - theta_g and m_g, back to
+        back, in class g mod 2; the anchor and M in whichever of classes 0 and 1 then holds fewer
+        of the outer step's buffers; v_g and grad_g, back to back, in class 2 while it has room,
+        else in the class of {0, 1} theta_g is not in.
       policy "pairs": theta_g, m_g in class g mod 3, v_g, grad_g in class (g + 1) mod 3, anchor
         and M where the fewest thetas are (the outer step's buffers then span three classes).
       policy "spread": class(theta_g) = g, class(m_g) = g + 1, class(v_g) = g + 2, class(grad_g) = g.
@@ -129,20 +130,30 @@ class PlacedState:
 
         self.P, self.M1, self.V, self.Gd = [], [], [], []
         if policy == "two_class":
-            two = min(2, ncls)
-            for g in range(G):          # theta_g and m_g allocated back to back
-                self.P.append(make(torch.float32, g % two))
-                self.M1.append(make(torch.float32, g % two))
-            make_outer([g % two for g in range(G)], list(range(two)))
+            # the library's own plan (pier_placement_plan), followed in the order it was made
+            if arena is not None:
+                from paper_2511_17849_amd import binding as _pier
+                plan, ca, cm = _pier.pier_placement_plan(arena.room(max(N, 1)), G, shared_grad, outer == "device")
+            else:
+                plan, ca, cm = [dict(theta=None, m=None, v=None, grad=None)] * G, None, None
+            for g in range(G):          # theta_g and m_g back to back
+                self.P.append(make(torch.float32, plan[g]["theta"]))
+                self.M1.append(make(torch.float32, plan[g]["m"]))
+            if outer == "device":
+                self.A, self.Mo = make(torch.float32, ca), make(torch.float32, cm)
+            elif outer == "pinned":
+                self.A = FlatList(self.numels, pinned=True, zero=False)
+                self.Mo = FlatList(self.numels, pinned=True, zero=False)
+            else:
+                self.A = self.Mo = None
             shared = None
-            for g in range(G):          # v_g and grad_g back to back, away from theta_g's class
-                away = [2, 1 - g % 2] if ncls >= 3 else [1 - g % 2]
-                self.V.append(make(torch.float32, away))
+            for g in range(G):          # v_g and grad_g back to back
+                self.V.append(make(torch.float32, plan[g]["v"]))
                 if shared_grad:
-                    shared = shared or make(grad_dtype, away)
+                    shared = shared or make(grad_dtype, plan[g]["grad"])
                     self.Gd.append(shared)
                 else:
-                    self.Gd.append(make(grad_dtype, away))
+                    self.Gd.append(make(grad_dtype, plan[g]["grad"]))
         else:
             if policy == "pairs":
                 kp, km, kv, kg = 0, 0, 1, 1

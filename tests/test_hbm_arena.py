@@ -38,6 +38,46 @@ def test_alloc_respects_classes_and_contiguity():
     assert all(e0 <= b1 for (_, e0), (b1, _) in zip(spans, spans[1:]))
 
 
+def test_room_counts_disjoint_runs_per_class():
+    a = fake_arena([0, 0, 0, 1, 1, 0, 2, 2, 2, 1])
+    assert a.room(256) == [4, 3, 3]                       # one granule each
+    assert a.room(512) == [1, 1, 1]                       # runs of two: 0-1, 3-4, 6-7
+    assert a.room(768) == [1, 0, 1]
+    a.alloc(256, torch.float32, cls=0)                    # takes granule 0
+    assert a.room(512) == [1, 1, 1] and a.room(768) == [0, 0, 1]
+    assert a.room(512, torch.bfloat16) == [3, 3, 3]       # 1024 bytes = one granule
+
+
+def test_placement_plan_of_the_library():
+    """pier_placement_plan (host arithmetic of libpier): every launch's buffers in two classes."""
+    import paper_2511_17849_amd as pier
+    reps, ca, cm = pier.pier_placement_plan([16, 16, 14], 8)
+    assert [r["theta"] for r in reps] == [0, 1] * 4 and all(r["m"] == r["theta"] for r in reps)
+    assert [r["v"] for r in reps] == [2] * 7 + [0] and all(r["grad"] == r["v"] for r in reps)
+    assert sorted([ca, cm]) == [0, 1]
+    # the 7B case: nine buffers fit; two gradient buffers cannot both be paired, one can
+    reps, ca, cm = pier.pier_placement_plan([3, 3, 3], 2, outer_on_device=False)
+    assert (ca, cm) == (-1, -1) and reps[0] == dict(theta=0, m=0, v=2, grad=2) and reps[1]["v"] == 2 and reps[1]["grad"] != 2
+    reps, _, _ = pier.pier_placement_plan([3, 3, 3], 2, shared_grad=True, outer_on_device=False)
+    assert all(r["v"] == 2 and r["grad"] == 2 for r in reps)
+    # fewer classes
+    reps, ca, cm = pier.pier_placement_plan([40], 2)
+    assert all(set(r.values()) == {0} for r in reps) and (ca, cm) == (0, 0)
+    reps, ca, cm = pier.pier_placement_plan([20, 20], 4)
+    assert [(r["theta"], r["v"]) for r in reps] == [(0, 1), (1, 0), (0, 1), (1, 0)] and sorted([ca, cm]) == [0, 1]
+    # odd group count: anchor and M even out the two classes
+    reps, ca, cm = pier.pier_placement_plan([16, 16, 14], 3)
+    assert (ca, cm) == (1, 0)
+    # a full class hands its buffers on; too little room altogether is an error
+    reps, ca, cm = pier.pier_placement_plan([2, 9, 9], 2)
+    assert reps[0]["theta"] == 0 and (ca, cm) == (1, 1)
+    with pytest.raises(pier.PierError, match="PIER_ERR_OOM"):
+        pier.pier_placement_plan([3, 3, 2], 2)
+    for bad in (dict(room=[], n_replicas=2), dict(room=[4, -1], n_replicas=1), dict(room=[4], n_replicas=0)):
+        with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+            pier.pier_placement_plan(**bad)
+
+
 def _placed(policy, G=8, classes=None, **kw):
     from pier_inputs import device as dev
     g = 4096                                             # granule bytes; one buffer = 3 granules
