@@ -104,6 +104,37 @@ def test_config3_gpt2_medium_bf16_gradients():
 
 
 @pytest.mark.timeout(600)
+def test_one_tensor_of_more_than_2_to_31_elements():
+    """Maximum sizes: a single tensor of 2^31 + 4099 elements (8.6 GB per buffer, element offsets
+    beyond 32 bits, byte offsets beyond 2^33, a ragged last chunk with a scalar tail) next to a small
+    one; G = 2.  Sampled densely around the 2^30, 2^31 and 2^32-byte marks of the big tensor."""
+    import pier_harness as H_
+    numels = [2 ** 31 + 4099, 1000]
+    marks = [2 ** 30, 2 ** 31 - 1024, 2 ** 31, 2 ** 31 + 1024, 2 ** 31 + 4096]
+    extra = np.concatenate([np.arange(m - 16, m + 16, dtype=np.int64) for m in marks] +
+                           [np.arange(numels[0] - 40, numels[0] + 40, dtype=np.int64)])
+    idx = np.unique(np.concatenate([H_.sample_indices(numels, chunk=1024), extra]))
+    _log("big tensor: N=%d sampled=%d" % (sum(numels), idx.size))
+    r = H_.Run(numels, 2, seed=41, sample=idx, shared_grad=True)
+    try:
+        r.inner_steps(1)
+        r.inner_steps(1, clip=1.0)
+        for norm_o, coef_o, norm_d, coef_d in r.clip_log:
+            assert abs(norm_d - norm_o) <= 0.5 * sum(numels) * 2.0 ** -53 * norm_o
+            assert abs(coef_d - coef_o) <= 6e-8 * coef_o and coef_o < 0.03
+        r.outer(mu=0.9, lr=1.1, phase=PIER)
+        rep = r.check("big tensor")
+        _log("big tensor: %s" % rep)
+        assert rep["bit_exact"], rep
+        r.outer(mu=0.9, lr=0.0, phase=WARMUP)
+        rep = r.check("big tensor, lazy start")
+        assert rep["bit_exact"], rep
+    finally:
+        del r
+        _free()
+
+
+@pytest.mark.timeout(600)
 def test_config3_shapes_clipped_steps_with_bf16_working_copies():
     """GPT-2 medium shapes, bf16 gradients, G = 8: two clipped inner steps (threshold 1, norm ~ 18.8)
     with bf16 working copies, then a Pier outer step; the oracle reduces every whole gradient on the host."""
