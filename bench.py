@@ -206,6 +206,16 @@ def main():
 
     inner_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / (K * G * H)     # per AdamW launch
     outer_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / K               # per outer launch
+    # after the timed region: 20 more outer steps timed one by one (a round has only one)
+    outer_each = []
+    if not host_outer:
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+        for e0, e1 in pairs:
+            e0.record(stream)
+            outer_step()
+            e1.record(stream)
+        torch.cuda.synchronize()
+        outer_each = sorted(e0.elapsed_time(e1) for e0, e1 in pairs)
     gbytes = 26 if bf16 else 28
     inner_gbps = gbytes * N / inner_ms / 1e6
     outer_bpe = 8 * G + 16
@@ -245,6 +255,9 @@ def main():
                            "algorithmic_GB_per_launch": outer_bpe * N / 1e9,
                            "bytes_per_param": outer_bpe, "avg_launch_ms": outer_ms, "launches_timed": K},
     }
+    if outer_each:
+        out["roofline_outer"].update({"median_launch_ms_of_20_more": outer_each[len(outer_each) // 2],
+                                      "min_max_launch_ms_of_20_more": [outer_each[0], outer_each[-1]]})
 
     if args.variants and not host_outer:
         def timed(fn, n):
