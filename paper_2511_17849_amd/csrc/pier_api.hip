@@ -231,6 +231,21 @@ pier_status check_all_bound(const pier_ctx* c)
     return PIER_OK;
 }
 
+// Word 3 of every outer-table row: alignment of the tensor's theta and working-copy pointers
+// over all replicas (the kernel for arbitrary group counts picks its vector path from it).
+void refresh_row_flags(pier_ctx* c)
+{
+    const size_t rw = outer_row_words(c->n_replicas);
+    for (int i = 0; i < c->n_tensors; ++i) {
+        uint64_t th = 0, wb = 0;
+        for (int r = 0; r < c->n_replicas; ++r) {
+            th |= c->h_rows[rw * i + kOuterRowHead + r];
+            wb |= c->h_rows[rw * i + kOuterRowHead + c->n_replicas + r];
+        }
+        c->h_rows[rw * i + 3] = ((th & 15u) == 0 ? 1u : 0u) | ((wb & 7u) == 0 ? 2u : 0u);
+    }
+}
+
 void free_plan(OffloadPlan& p)
 {
     if (p.d_chunks) (void)hipFree(p.d_chunks);
@@ -379,6 +394,7 @@ pier_status pier_bind_replica(pier_ctx* c, int replica, float* const* p, float* 
     const size_t rw = outer_row_words(c->n_replicas);
     for (int i = 0; i < c->n_tensors; ++i)
         c->h_rows[rw * i + kOuterRowHead + replica] = reinterpret_cast<uint64_t>(p[i]);
+    refresh_row_flags(c);
     PIER_HIP(hipMemcpy(c->d_rows, c->h_rows.data(), sizeof(uint64_t) * c->h_rows.size(),
                        hipMemcpyHostToDevice));
     c->rep_bound[replica] = 1;
@@ -402,6 +418,7 @@ pier_status pier_bind_shadow(pier_ctx* c, int replica, uint16_t* const* w_bf16)
         row[i].w = w_bf16 ? w_bf16[i] : nullptr;
         c->h_rows[rw * i + kOuterRowHead + c->n_replicas + replica] = reinterpret_cast<uint64_t>(row[i].w);
     }
+    refresh_row_flags(c);
     PIER_HIP(hipMemcpy(c->d_rep + static_cast<size_t>(replica) * c->n_tensors, row,
                        sizeof(RepPtrs) * c->n_tensors, hipMemcpyHostToDevice));
     PIER_HIP(hipMemcpy(c->d_rows, c->h_rows.data(), sizeof(uint64_t) * c->h_rows.size(),

@@ -31,7 +31,9 @@ struct RepPtrs {
 //   word 0: anchor pointer   word 1: momentum pointer
 //   word 2: flat_start = number of elements in the tensors before this one (its
 //           position in the flat host arrays of the offload path)
-//   word 3: reserved         words 4 .. 4+G-1: theta pointers of replicas 0 .. G-1
+//   word 3: flags, bit 0 = every bound theta pointer of the tensor is 16-byte aligned,
+//           bit 1 = every bound working-copy pointer is 8-byte aligned
+//   words 4 .. 4+G-1: theta pointers of replicas 0 .. G-1
 //   words 4+G .. 4+2G-1: bfloat16 working-copy pointers of the replicas (or null)
 constexpr int kOuterRowHead = 4;
 inline size_t outer_row_words(int G) { return static_cast<size_t>(kOuterRowHead + 2 * G); }

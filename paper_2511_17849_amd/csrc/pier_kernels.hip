@@ -507,7 +507,7 @@ struct OuterRow {
     float* a;
     float* M;
     int64_t flat_start;
-    int64_t reserved;
+    uint64_t flags;     // alignment summary for the kernel of arbitrary group counts
     float* th[G];
     unsigned short* wb[G];
 };
@@ -608,17 +608,51 @@ __global__ __launch_bounds__(WG) void outer_kernel(const Chunk* __restrict__ chu
     }
 }
 
-// Any number of groups: the replicas are walked in a run-time loop (same order,
-// same arithmetic), one element per lane.  Covers the group counts without a
-// specialised kernel.
-template <bool FLAT, bool PIER>
-__global__ __launch_bounds__(kBlock) void outer_kernel_anyG(const Chunk* __restrict__ chunks,
-                                                            const uint64_t* __restrict__ rows,
-                                                            OuterArgs A)
+// Any number of groups: the replicas are walked in a run-time loop (same order, same
+// arithmetic).  Where every stream of the chunk is 16-byte aligned (the host records that per
+// tensor in word 3 of the row: bit 0 for the theta pointers, bit 1 for the working copies),
+// lanes move 128-bit vectors and keep up to eight replica loads in flight; otherwise one
+// element per lane.  Covers the group counts without a specialised kernel.
+template <bool PIER>
+__device__ __forceinline__ void outer_anyG_scalar(const uint64_t* __restrict__ row, const OuterArgs& A,
+                                                  float* a, float* M, int64_t off, int i)
 {
 #pragma clang fp contract(off)
-    const int tid = threadIdx.x;
-    for (int c = blockIdx.x; c < A.n_chunks; c += gridDim.x) {
+    const float av = ld<false>(a + i);
+    float s = 0.0f, s2 = 0.0f;
+    for (int g = 0; g < A.G; ++g) {
+        const float t = ld<false>(reinterpret_cast<const float*>(row[kOuterRowHead + g]) + off + i);
+        s = s + (t - av);
+        s2 = s2 + t;
+    }
+    const float d = s * A.invG;
+    const float Mn = A.mu * ld<false>(M + i) + d;
+    st<false>(M + i, Mn);
+    if constexpr (PIER) {
+        const float x = av + A.lr * (A.mu * Mn + d);
+        st<false>(a + i, x);
+        for (int g = 0; g < A.G; ++g)
+            st<false>(reinterpret_cast<float*>(row[kOuterRowHead + g]) + off + i, x);
+        if (A.shadow) {
+            const unsigned short h = f32_to_bf16(x);
+            for (int g = 0; g < A.G; ++g)
+                st<false>(reinterpret_cast<unsigned short*>(row[kOuterRowHead + A.G + g]) + off + i, h);
+        }
+    } else {
+        st<false>(a + i, s2 * A.invG);
+    }
+}
+
+template <int WG, bool FLAT, bool PIER, bool NT>
+__global__ __launch_bounds__(WG) void outer_kernel_anyG(const Chunk* __restrict__ chunks,
+                                                        const uint64_t* __restrict__ rows,
+                                                        OuterArgs A)
+{
+#pragma clang fp contract(off)
+    constexpr int kBatch = 8;   // replica loads in flight per lane
+    const Team<WG> team;
+    const int tid = team.lane;
+    for (int c = team.first; c < A.n_chunks; c += team.stride) {
         const Chunk ch = chunks[c];
         const uint64_t* __restrict__ row = rows + static_cast<int64_t>(ch.tensor) * (kOuterRowHead + 2 * A.G);
         float* __restrict__ a;
@@ -631,30 +665,50 @@ __global__ __launch_bounds__(kBlock) void outer_kernel_anyG(const Chunk* __restr
             a = reinterpret_cast<float*>(row[0]) + ch.off;
             M = reinterpret_cast<float*>(row[1]) + ch.off;
         }
-        for (int i = tid; i < ch.len; i += kBlock) {
-            const float av = ld<false>(a + i);
-            float s = 0.0f, s2 = 0.0f;
-            for (int g = 0; g < A.G; ++g) {
-                const float t = ld<false>(reinterpret_cast<const float*>(row[kOuterRowHead + g]) + ch.off + i);
-                s = s + (t - av);
-                s2 = s2 + t;
-            }
-            const float d = s * A.invG;
-            const float Mn = A.mu * ld<false>(M + i) + d;
-            st<false>(M + i, Mn);
-            if constexpr (PIER) {
-                const float x = av + A.lr * (A.mu * Mn + d);
-                st<false>(a + i, x);
-                for (int g = 0; g < A.G; ++g)
-                    st<false>(reinterpret_cast<float*>(row[kOuterRowHead + g]) + ch.off + i, x);
-                if (A.shadow) {
-                    const unsigned short h = f32_to_bf16(x);
-                    for (int g = 0; g < A.G; ++g)
-                        st<false>(reinterpret_cast<unsigned short*>(row[kOuterRowHead + A.G + g]) + ch.off + i, h);
+        const uint64_t flags = row[3];
+        const bool vec = (flags & 1u) && (ch.off & 3) == 0 &&
+                         ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(M)) & 15u) == 0 &&
+                         (!A.shadow || (flags & 2u));
+        if (vec) {
+            const int n4 = ch.len >> 2;
+            for (int j = tid; j < n4; j += kBlock) {
+                const unsigned o = static_cast<unsigned>(j) * 16u;
+                vfloat4 Av = ldo<NT, vfloat4>(a, o), Mv = ldo<NT, vfloat4>(M, o);
+                vfloat4 s = {0.0f, 0.0f, 0.0f, 0.0f}, s2 = {0.0f, 0.0f, 0.0f, 0.0f};
+                for (int g0 = 0; g0 < A.G; g0 += kBatch) {
+                    vfloat4 T[kBatch];
+#pragma unroll
+                    for (int k = 0; k < kBatch; ++k)
+                        if (g0 + k < A.G)
+                            T[k] = ldo<NT, vfloat4>(reinterpret_cast<const float*>(row[kOuterRowHead + g0 + k]) + ch.off, o);
+#pragma unroll
+                    for (int k = 0; k < kBatch; ++k)
+                        if (g0 + k < A.G) {
+                            s = s + (T[k] - Av);
+                            s2 = s2 + T[k];
+                        }
                 }
-            } else {
-                st<false>(a + i, s2 * A.invG);
+                const vfloat4 d = s * A.invG;
+                const vfloat4 Mn = A.mu * Mv + d;
+                sto<NT>(M, o, Mn);
+                if constexpr (PIER) {
+                    const vfloat4 x = Av + A.lr * (A.mu * Mn + d);
+                    sto<NT>(a, o, x);
+                    for (int g = 0; g < A.G; ++g)
+                        sto<NT>(reinterpret_cast<float*>(row[kOuterRowHead + g]) + ch.off, o, x);
+                    if (A.shadow) {
+                        const vushort4 h = f32_to_bf16(x);
+                        for (int g = 0; g < A.G; ++g)
+                            sto<NT>(reinterpret_cast<unsigned short*>(row[kOuterRowHead + A.G + g]) + ch.off, o >> 1, h);
+                    }
+                } else {
+                    sto<NT>(a, o, s2 * A.invG);
+                }
             }
+            const int i = (n4 << 2) + tid;      // up to three elements past the last whole vector
+            if (i < ch.len) outer_anyG_scalar<PIER>(row, A, a, M, ch.off, i);
+        } else {
+            for (int i = tid; i < ch.len; i += kBlock) outer_anyG_scalar<PIER>(row, A, a, M, ch.off, i);
         }
     }
 }
@@ -711,10 +765,19 @@ static void outer_dispatch_g(int grid, const OuterTables& T, const OuterArgs& A,
     case 2: outer_dispatch_u<2, FLAT, PIER>(grid, T, A, shape, stream); break;
     case 4: outer_dispatch_u<4, FLAT, PIER>(grid, T, A, shape, stream); break;
     case 8: outer_dispatch_u<8, FLAT, PIER>(grid, T, A, shape, stream); break;
-    default:
-        hipLaunchKernelGGL((outer_kernel_anyG<FLAT, PIER>), dim3(grid), dim3(kBlock),
-                           static_cast<unsigned>(shape.lds_bytes), stream, T.chunks, T.rows, A);
+    default: {
+        const unsigned lds = static_cast<unsigned>(shape.lds_bytes);
+        if (shape.wg_threads == 64) {
+            const dim3 g(static_cast<unsigned>(grid) * (kBlock / 64)), b(64);
+            if (shape.nontemporal) hipLaunchKernelGGL((outer_kernel_anyG<64, FLAT, PIER, true>), g, b, lds, stream, T.chunks, T.rows, A);
+            else hipLaunchKernelGGL((outer_kernel_anyG<64, FLAT, PIER, false>), g, b, lds, stream, T.chunks, T.rows, A);
+        } else {
+            const dim3 g(static_cast<unsigned>(grid)), b(kBlock);
+            if (shape.nontemporal) hipLaunchKernelGGL((outer_kernel_anyG<kBlock, FLAT, PIER, true>), g, b, lds, stream, T.chunks, T.rows, A);
+            else hipLaunchKernelGGL((outer_kernel_anyG<kBlock, FLAT, PIER, false>), g, b, lds, stream, T.chunks, T.rows, A);
+        }
         break;
+    }
     }
 }
 

@@ -336,6 +336,29 @@ def test_offload_with_odd_sized_tensors():
         assert np.array_equal(a[k], b[k]), k
 
 
+@pytest.mark.parametrize("G", [3, 6, 9, 16, 33, 64])
+def test_group_counts_without_a_specialised_kernel(G):
+    """Group counts other than 1, 2, 4, 8 (the paper runs 8, 32 and 64 groups) go through the
+    kernel that walks the replicas in a run-time loop: vector path on aligned tensors, scalar
+    path on misaligned ones and on tails, resident and offloaded, with bf16 working copies."""
+    H_ = _harness()
+    numels = [4096 * 3, 1025, 7, 0, 20_000, 1024, 3]
+    _log("any-G outer step, G=%d" % G)
+    res = H_.Run(numels, G, seed=100 + G, shadow=(G % 2 == 1))
+    off = H_.Run(numels, G, seed=100 + G, offload=True, chunk_bytes=40_000, shadow=(G % 2 == 1))
+    pad = H_.Run(numels, G, seed=100 + G, pad=1, launch=dict(wg_threads=256, lds_bytes=0))
+    for r in (res, off, pad):
+        r.inner_steps(1, shared_stream=True)
+        r.outer(mu=0.9, lr=0.0, phase=WARMUP)
+        r.inner_steps(2)
+        r.outer(mu=0.99, lr=0.8, phase=PIER)
+        rep = r.check("G=%d" % G)
+        assert rep["bit_exact"], rep
+    a, b = res.device_state(), off.device_state()
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+
+
 # ------------------------------------------------------------------ error paths (host-side checks)
 
 def test_argument_errors_are_reported_not_launched():
