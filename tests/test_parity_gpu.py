@@ -114,6 +114,11 @@ def test_grad_scale_and_other_hyperparameters():
     r.inner_steps(5)
     r.outer(mu=0.0, lr=1.0, phase=PIER)
     r.check("grad_scale")
+    # late in training the bias corrections are exactly 1 (beta^t underflows against 1)
+    r.t = 999_999
+    r.inner_steps(2)
+    rep = r.check("step one million")
+    assert rep["bit_exact"], rep
 
 
 @pytest.mark.parametrize("case", range(8))
