@@ -133,3 +133,85 @@ def test_pairs_and_spread_policies_on_a_linear_three_class_arena():
     _no_overlap(s)
     s, P, M, V, Gd, _ = _placed("spread", G=3)
     assert P == [0, 1, 2] and M == [1, 2, 0] and V == [2, 0, 1] and Gd == P
+
+
+# ---------------------------------------------------------------- randomised host-logic checks
+
+def test_plan_never_overfills_a_class_and_keeps_launches_in_two_classes_when_room_allows():
+    import numpy as np
+    import paper_2511_17849_amd as pier
+    rng = np.random.default_rng(5)
+    for _ in range(400):
+        ncls = int(rng.integers(1, 5))
+        G = int(rng.integers(1, 17))
+        shared = bool(rng.integers(0, 2))
+        outer = bool(rng.integers(0, 2))
+        need = 3 * G + (1 if shared else G) + (2 if outer else 0)
+        room = [int(x) for x in rng.integers(0, 2 * need // ncls + 3, ncls)]
+        try:
+            reps, ca, cm = pier.pier_placement_plan(room, G, shared_grad=shared, outer_on_device=outer)
+        except pier.PierError as e:
+            assert "PIER_ERR_OOM" in str(e)
+            # the plan gives up only when whole buffers cannot be placed one by one either:
+            # that can only happen when the total room is short
+            assert sum(room) < need, (room, G, shared, outer)
+            continue
+        used = [0] * ncls
+        grads = set()
+        for g, r in enumerate(reps):
+            for k in ("theta", "m", "v"):
+                assert 0 <= r[k] < ncls
+                used[r[k]] += 1
+            assert 0 <= r["grad"] < ncls
+            if shared:
+                grads.add(r["grad"])
+            else:
+                used[r["grad"]] += 1
+        if shared:
+            assert len(grads) == 1
+            used[grads.pop()] += 1
+        if outer:
+            used[ca] += 1
+            used[cm] += 1
+        else:
+            assert (ca, cm) == (-1, -1)
+        assert all(u <= r for u, r in zip(used, room)), (room, used)
+        assert sum(used) == need
+        # with generous room every AdamW launch is two-and-two over two classes (or one class
+        # when there is only one), and the outer step's buffers split evenly over two
+        if ncls >= 2 and min(room) >= need:
+            for r in reps:
+                assert r["theta"] == r["m"] and r["v"] == r["grad"] and r["v"] != r["theta"]
+            if outer:
+                o = [r["theta"] for r in reps] + [ca, cm]
+                assert abs(o.count(0) - o.count(1)) <= 1 and o.count(0) + o.count(1) == G + 2
+
+
+def test_arena_random_allocation_never_overlaps_and_room_is_honest():
+    import numpy as np
+    rng = np.random.default_rng(6)
+    for _ in range(100):
+        n = int(rng.integers(8, 80))
+        classes = list(np.repeat(rng.integers(0, 3, 8), rng.integers(1, 12, 8))[:n])
+        if len(set(classes)) != max(classes) + 1:
+            continue                                        # class ids must be dense
+        a = fake_arena(classes, granule=64)
+        spans = []
+        for _ in range(30):
+            numel = int(rng.integers(1, 80))
+            cls = None if rng.random() < 0.3 else int(rng.integers(0, 4))
+            room = a.room(numel)
+            try:
+                t, c = a.alloc(numel, torch.float32, cls)
+            except MemoryError:
+                assert sum(room) == 0                       # nothing fitted anywhere
+                continue
+            assert sum(room) > 0
+            if cls is not None and room[cls % a.n_classes] > 0:
+                assert c == cls % a.n_classes               # the asked class when it had a run
+            lo = t.data_ptr() - a.buf.data_ptr()
+            hi = lo + numel * 4
+            g0, g1 = lo // 64, (hi - 1) // 64
+            assert lo % 64 == 0 and all(a.classes[g] == c for g in range(g0, g1 + 1))
+            assert all(hi <= s or e <= lo for s, e in spans)
+            spans.append((g0 * 64, (g1 + 1) * 64))
