@@ -40,7 +40,9 @@ def parse():
     ap.add_argument("--no-offload", action="store_true", help="skip the host-offload measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-arena", action="store_true", help="plain allocations instead of the probed arena")
-    ap.add_argument("--chunk-mib", type=int, default=256, help="offload piece size")
+    ap.add_argument("--chunk-mib", type=int, default=0,
+                    help="offload piece size; 0 = 256 MiB, or a sixteenth of one array (in steps of "
+                         "16 MiB) when that is smaller, so that small models still fill the pipeline")
     ap.add_argument("--variants", action="store_true",
                     help="also time the clipped step, the bf16-working-copy kernels and the lazy-start outer step")
     return ap.parse_args()
@@ -164,6 +166,8 @@ def main():
     ctx = pier.pier_ctx_create(w.numels, G)
     for g in range(G):
         pier.pier_bind_replica(ctx, g, P[g].tensors, M1[g].tensors, V[g].tensors, Gd[g].tensors, bf16)
+    if args.chunk_mib <= 0:
+        args.chunk_mib = min(256, max(16, -(-(4 * N // 16) // (16 << 20)) * 16))
     chunk = args.chunk_mib << 20
     if host_outer:
         pier.pier_bind_outer(ctx, pier.PIER_LOC_HOST_PINNED, A.flat, Mo.flat)
