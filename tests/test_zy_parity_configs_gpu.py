@@ -104,6 +104,29 @@ def test_config3_gpt2_medium_bf16_gradients():
 
 
 @pytest.mark.timeout(600)
+def test_sixty_four_groups_at_gpt2_small_size():
+    """The paper's largest group count (64) at GPT-2 small shapes: 64 models of 124 M parameters
+    (32 GB) through the outer kernel for arbitrary group counts, lazy-start and Pier phases."""
+    import pier_harness as H_
+    from pier_inputs import shapes
+    w = shapes.workloads()["gpt2_small"]
+    idx = H_.sample_indices(w.numels, chunk=1024)
+    _log("64 groups: N=%d sampled=%d" % (w.N, idx.size))
+    r = H_.Run(w.numels, 64, seed=64, sample=idx, shared_grad=True)
+    try:
+        r.inner_steps(1, shared_stream=True)
+        r.outer(mu=0.9, lr=0.0, phase=WARMUP)
+        r.inner_steps(1)
+        r.outer(mu=0.99, lr=0.4, phase=PIER)
+        rep = r.check("64 groups")
+        _log("64 groups: %s" % rep)
+        assert rep["bit_exact"], rep
+    finally:
+        del r
+        _free()
+
+
+@pytest.mark.timeout(600)
 def test_one_tensor_of_more_than_2_to_31_elements():
     """Maximum sizes: a single tensor of 2^31 + 4099 elements (8.6 GB per buffer, element offsets
     beyond 32 bits, byte offsets beyond 2^33, a ragged last chunk with a scalar tail) next to a small
