@@ -48,6 +48,11 @@ typedef enum {
     PIER_ERR_HIP = 5          /* the HIP runtime reported an error (text in last_error) */
 } pier_status;
 
+/* Version of this interface: PIER_ABI_VERSION of the header the library was built from.
+ * It changes whenever a declared function, struct or enum changes incompatibly. */
+#define PIER_ABI_VERSION 1
+int pier_abi_version(void);
+
 /* Text of the calling thread's most recent error; never NULL; valid until the
  * thread's next failing call. */
 const char* pier_last_error(void);

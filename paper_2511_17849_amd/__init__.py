@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     pier_offload_workspace_bytes, pier_offload_stream, pier_hbm_probe, pier_placement_plan,
     pier_mu_schedule, pier_outer_lr_schedule, pier_outer_schedule,
     pier_inner_lr_schedule, pier_train_step, TrainCfg, PIER_MODE_PIER, PIER_MODE_DILOCO,
-    pier_last_error, pier_status_string, library_path,
+    pier_last_error, pier_status_string, library_path, pier_abi_version,
 )
 from .hbm_arena import HbmArena  # noqa: F401

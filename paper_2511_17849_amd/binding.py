@@ -73,6 +73,7 @@ def _load():
     vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
     pp = ctypes.POINTER(ctypes.c_void_p)
     sig = {
+        "pier_abi_version": (i32, []),
         "pier_last_error": (ctypes.c_char_p, []),
         "pier_status_string": (ctypes.c_char_p, [i32]),
         "pier_ctx_create": (i32, [ctypes.POINTER(vp), i32, ctypes.POINTER(i64), i32]),
@@ -102,6 +103,9 @@ def _load():
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
         fn.restype, fn.argtypes = res, args
+    if L.pier_abi_version() != ABI_VERSION:
+        raise ImportError("libpier.so has ABI version %d, this binding expects %d: rebuild with "
+                          "`python -m paper_2511_17849_amd.build`" % (L.pier_abi_version(), ABI_VERSION))
     _lib = L
     return L
 
@@ -247,6 +251,13 @@ def pier_offload_stream(ctx, *, outer_lr, mu, phase, chunk_bytes, workspace, com
                                        int(wbytes), _stream(compute_stream), _stream(h2d_stream),
                                        _stream(d2h_stream), ctypes.byref(stats) if want_stats else None))
     return stats
+
+
+ABI_VERSION = 1     # PIER_ABI_VERSION of the header this binding was written against
+
+
+def pier_abi_version():
+    return _load().pier_abi_version()
 
 
 def pier_placement_plan(room, n_replicas, shared_grad=False, outer_on_device=True):

@@ -258,6 +258,8 @@ void free_plan(OffloadPlan& p)
 
 extern "C" {
 
+int pier_abi_version(void) { return PIER_ABI_VERSION; }
+
 const char* pier_last_error(void) { return g_last_error.c_str(); }
 
 const char* pier_status_string(pier_status s)
