@@ -2,8 +2,10 @@
 // step and the fused outer step of Pier's two-level optimizer.
 //
 // Both kernels are elementwise streams bound by HBM bandwidth, so the design is:
-//   * one workgroup of 4 wavefronts per chunk of a tensor (chunk table in device
-//     memory, read through the scalar unit because the index is wave-uniform);
+//   * a team of 4 wavefronts per chunk of a tensor (chunk table in device memory, read
+//     through the scalar unit because the index is wave-uniform), launched as one
+//     workgroup or, by default, as four one-wave workgroups with a cap on the waves
+//     resident per compute unit: both kernels stream faster with few waves in flight;
 //   * 128-bit loads/stores, lane i of a wavefront touching vector i of a 1 KiB run,
 //     so every wave-level access is one fully coalesced 1 KiB burst per stream;
 //   * all loads of a tile (UNROLL vectors x every stream) are issued before the
