@@ -762,7 +762,11 @@ static void outer_dispatch_u(int grid, const OuterTables& T, const OuterArgs& A,
 template <bool FLAT, bool PIER>
 static void outer_dispatch_g(int grid, const OuterTables& T, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
 {
-    switch (A.G) {
+    // The register-array kernels win for up to four groups in both phases and for eight groups
+    // in the Pier phase (1-10 % over the loop kernel); the lazy-start phase over eight groups
+    // (ten read streams, two written) measured 0.5-1 % faster in the loop kernel.
+    const bool loop_kernel = !PIER && A.G == 8 && shape.unroll == 1;
+    switch (loop_kernel ? 0 : A.G) {
     case 1: outer_dispatch_u<1, FLAT, PIER>(grid, T, A, shape, stream); break;
     case 2: outer_dispatch_u<2, FLAT, PIER>(grid, T, A, shape, stream); break;
     case 4: outer_dispatch_u<4, FLAT, PIER>(grid, T, A, shape, stream); break;
