@@ -208,6 +208,36 @@ def test_config4_gpt2_xl_clipped_step():
     _free()
 
 
+@pytest.mark.timeout(300)
+def test_placement_probe_is_repeatable_and_rejects_bad_arguments():
+    """pier_hbm_probe on (nearly) the whole HBM: dense class ids, a few large classes (three of
+    about 96 GiB on a 288 GiB MI355X), the same map when asked again; argument errors launch
+    nothing."""
+    import paper_2511_17849_amd as pier
+    a = _arena()
+    try:
+        cls = list(a.classes)
+        assert sorted(set(cls)) == list(range(max(cls) + 1)) and 1 <= a.n_classes <= 6
+        sizes = [cls.count(c) * a.granule / 2 ** 30 for c in range(a.n_classes)]
+        _log("probe: %d classes of %s GiB" % (a.n_classes, [round(x) for x in sizes]))
+        assert min(sizes) >= 8                                  # no stray one-granule classes
+        again = pier.pier_hbm_probe(a.buf, a.granule)
+        # the same partition up to the numbering of the classes; a few granules at class boundaries
+        # may fall the other way between runs
+        relabel = {c: max(set(again), key=lambda d: sum(1 for x, y in zip(cls, again) if x == c and y == d))
+                   for c in set(cls)}
+        flips = sum(1 for x, y in zip(cls, again) if relabel[x] != y)
+        assert flips <= max(3, len(cls) // 30), (cls, again)
+        for bad in (dict(granule_bytes=1 << 20), dict(granule_bytes=(512 << 20) + 4096)):
+            with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+                pier.pier_hbm_probe(a.buf, **bad)
+        with pytest.raises(pier.PierError):
+            pier.pier_hbm_probe(torch.empty(1 << 20, dtype=torch.uint8), a.granule)   # host memory
+    finally:
+        del a
+        _free()
+
+
 @pytest.mark.timeout(600)
 def test_config4_gpt2_xl_in_probed_arena():
     arena = _arena()
