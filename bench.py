@@ -43,6 +43,10 @@ def parse():
     ap.add_argument("--chunk-mib", type=int, default=0,
                     help="offload piece size; 0 = 256 MiB, or a sixteenth of one array (in steps of "
                          "16 MiB) when that is smaller, so that small models still fill the pipeline")
+    ap.add_argument("--offload-slots", type=int, default=0,
+                    help="staging slots of the offload stream (0: 3, or 20 when the outer state lives on the host)")
+    ap.add_argument("--no-trailing", action="store_true",
+                    help="host-offload workloads: make the compute stream wait for the copy-back")
     ap.add_argument("--variants", action="store_true",
                     help="also time the clipped step, the bf16-working-copy kernels and the lazy-start outer step")
     return ap.parse_args()
@@ -129,6 +133,14 @@ def main():
     lr_o, mu = w.fixed_outer or (1.1, 0.9)
     stream = torch.cuda.Stream()
 
+    if args.chunk_mib <= 0:
+        args.chunk_mib = min(256, max(16, -(-(4 * N // 16) // (16 << 20)) * 16))
+    chunk = args.chunk_mib << 20
+    # a workload whose outer step IS the offload stream runs it with trailing write-back: the next
+    # round's inner steps start as soon as the last piece's kernel is done, the copy-back of the
+    # last pieces overlaps them; that needs staging for the backlog the slower copy-back builds up
+    offload_slots = args.offload_slots or (20 if w.offload else 3)
+
     # HBM layout: one arena over (almost) all free HBM is probed for its address classes and
     # the buffers one launch streams together are carved from different classes; if the
     # arena cannot be had, buffers are allocated kind by kind instead
@@ -137,7 +149,7 @@ def main():
     if not args.no_arena:
         try:
             free, _ = torch.cuda.mem_get_info()
-            arena = pier.HbmArena(free - (8 << 30), stream=stream)
+            arena = pier.HbmArena(free - (8 << 30) - (offload_slots * 2 * chunk if w.offload else 0), stream=stream)
             placement = "probed arena of %d GiB, %d address classes" % (arena.buf.numel() >> 30, arena.n_classes)
         except (MemoryError, RuntimeError, pier.PierError) as e:
             print("bench.py: no arena (%s); allocating kind by kind" % e, file=sys.stderr)
@@ -166,13 +178,11 @@ def main():
     ctx = pier.pier_ctx_create(w.numels, G)
     for g in range(G):
         pier.pier_bind_replica(ctx, g, P[g].tensors, M1[g].tensors, V[g].tensors, Gd[g].tensors, bf16)
-    if args.chunk_mib <= 0:
-        args.chunk_mib = min(256, max(16, -(-(4 * N // 16) // (16 << 20)) * 16))
-    chunk = args.chunk_mib << 20
     if host_outer:
         pier.pier_bind_outer(ctx, pier.PIER_LOC_HOST_PINNED, A.flat, Mo.flat)
-        ws = torch.empty(pier.pier_offload_workspace_bytes(ctx, chunk), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(2 * chunk * offload_slots, dtype=torch.uint8, device="cuda")
         s_in, s_out = torch.cuda.Stream(), torch.cuda.Stream()
+        pier.pier_ctx_set_offload_writeback(ctx, 0 if args.no_trailing else 1)
     else:
         pier.pier_bind_outer(ctx, pier.PIER_LOC_DEVICE, A.tensors, Mo.tensors)
 
@@ -236,7 +246,9 @@ def main():
         "config": {"workload": "%s: N=%d fp32 params in %d tensors, G=%d replicas, H=%d inner steps per "
                                "round, %s outer step (mu=%.2f, outer lr=%.2f)" %
                                (w.name, N, len(w.numels), G, H,
-                                "host-offload (PCIe-inclusive, %d MiB pieces)" % args.chunk_mib if host_outer
+                                "host-offload (PCIe-inclusive, %d MiB pieces, %d staging slots, %s write-back)" %
+                                (args.chunk_mib, offload_slots, "blocking" if args.no_trailing else "trailing")
+                                if host_outer
                                 else "resident", mu, lr_o),
                    "hbm_placement": placement},
         # the paper publishes no figure for this path (hence vs_baseline null); its own numbers are
@@ -315,6 +327,7 @@ def main():
             pier.pier_bind_outer(ctx, pier.PIER_LOC_HOST_PINNED, hA, hM)
             ws = torch.empty(pier.pier_offload_workspace_bytes(ctx, chunk), dtype=torch.uint8, device="cuda")
             s_in, s_out = torch.cuda.Stream(), torch.cuda.Stream()
+        pier.pier_ctx_set_offload_writeback(ctx, 0)
         best = None
         for _ in range(3):
             st = pier.pier_offload_stream(ctx, outer_lr=lr_o, mu=mu, phase=pier.PIER_PHASE_PIER,
@@ -327,7 +340,7 @@ def main():
             "slots": best.n_slots, "wall_ms": best.wall_ms,
             "h2d_GBps": best.h2d_bytes / best.h2d_ms / 1e6, "d2h_GBps": best.d2h_bytes / best.d2h_ms / 1e6,
             "pcie_GBps_each_way_over_wall": best.h2d_bytes / best.wall_ms / 1e6,
-            "kernel_ms": best.kernel_ms,
+            "kernel_ms": best.kernel_ms, "first_reload_to_last_kernel_ms": best.compute_ms,
             "overlap": max(best.h2d_ms, best.d2h_ms, best.kernel_ms) / best.wall_ms,
             "params_per_s": N / best.wall_ms * 1e3,
         }

@@ -50,7 +50,7 @@ typedef enum {
 
 /* Version of this interface: PIER_ABI_VERSION of the header the library was built from.
  * It changes whenever a declared function, struct or enum changes incompatibly. */
-#define PIER_ABI_VERSION 1
+#define PIER_ABI_VERSION 2
 int pier_abi_version(void);
 
 /* Text of the calling thread's most recent error; never NULL; valid until the
@@ -178,7 +178,7 @@ pier_status pier_outer_step(pier_ctx* ctx, const pier_outer_hp* hp, void* hip_st
  * intended size); piece k is copied host->device on h2d_stream, processed by the
  * outer kernel on compute_stream and copied back on d2h_stream, the three stages of
  * different pieces overlapping.  `workspace` is caller-owned device memory holding
- * the staging slots (2 arrays x chunk_bytes per slot; 1 to 4 slots are used, 3
+ * the staging slots (2 arrays x chunk_bytes per slot; 1 to 64 slots are used, 3
  * recommended = pier_offload_workspace_bytes).  Results are bit-identical to
  * pier_outer_step.  compute_stream is made to wait for the last copy-back, so work
  * enqueued on it afterwards sees both the replicas and the host arrays complete; the
@@ -191,8 +191,18 @@ pier_status pier_outer_step(pier_ctx* ctx, const pier_outer_hp* hp, void* hip_st
 typedef struct {
     double h2d_bytes, d2h_bytes, h2d_ms, d2h_ms, kernel_ms, wall_ms;
     int n_pieces, n_slots;
+    double compute_ms; /* first reload to last kernel: what compute_stream waits for in trailing mode */
 } pier_offload_stats;
 pier_status pier_offload_workspace_bytes(const pier_ctx* ctx, size_t chunk_bytes, size_t* out);
+/* When the write-back may finish.  trailing = 0 (default): as described above,
+ * compute_stream waits for the last copy-back.  trailing = 1: it does not - the replicas
+ * are final when compute_stream has passed the call's kernels, so the next inner steps
+ * start while the copy-back still runs; the host arrays and the workspace are final when
+ * d2h_stream has drained, and the caller leaves both alone until then (the next
+ * pier_offload_stream call waits for it by itself).  Pays off when the workspace holds
+ * enough slots for the reload to run ahead of the slower copy-back (up to 64 are used;
+ * about 7 GB of backlog builds up over the 7B model's 53 GB).  Results do not change. */
+pier_status pier_ctx_set_offload_writeback(pier_ctx* ctx, int trailing);
 pier_status pier_offload_stream(pier_ctx* ctx, const pier_outer_hp* hp, size_t chunk_bytes,
                                 void* workspace, size_t workspace_bytes, void* compute_stream,
                                 void* h2d_stream, void* d2h_stream, pier_offload_stats* stats);

@@ -4,7 +4,7 @@ There is no CPU fallback: loading fails loudly when the library has not been bui
 from .binding import (  # noqa: F401
     PierError, PierCtx, AdamwHP, OuterHP, OffloadStats,
     PIER_PHASE_WARMUP, PIER_PHASE_PIER, PIER_LOC_DEVICE, PIER_LOC_HOST_PINNED,
-    pier_ctx_create, pier_ctx_destroy, pier_ctx_numel, pier_ctx_set_launch, pier_ctx_set_occupancy,
+    pier_ctx_create, pier_ctx_destroy, pier_ctx_numel, pier_ctx_set_launch, pier_ctx_set_occupancy, pier_ctx_set_offload_writeback,
     pier_bind_replica, pier_bind_shadow, pier_bind_outer, pier_inner_adamw, pier_outer_step,
     pier_inner_adamw_clipped, pier_grad_norm_last,
     pier_offload_workspace_bytes, pier_offload_stream, pier_hbm_probe, pier_placement_plan,

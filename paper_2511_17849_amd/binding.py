@@ -43,7 +43,7 @@ class OffloadStats(ctypes.Structure):
     _fields_ = [("h2d_bytes", ctypes.c_double), ("d2h_bytes", ctypes.c_double),
                 ("h2d_ms", ctypes.c_double), ("d2h_ms", ctypes.c_double),
                 ("kernel_ms", ctypes.c_double), ("wall_ms", ctypes.c_double),
-                ("n_pieces", ctypes.c_int), ("n_slots", ctypes.c_int)]
+                ("n_pieces", ctypes.c_int), ("n_slots", ctypes.c_int), ("compute_ms", ctypes.c_double)]
 
 
 _lib = None
@@ -81,6 +81,7 @@ def _load():
         "pier_ctx_numel": (i64, [vp]),
         "pier_ctx_set_launch": (i32, [vp, i64, i32, i32, i32]),
         "pier_ctx_set_occupancy": (i32, [vp, i32, i32]),
+        "pier_ctx_set_offload_writeback": (i32, [vp, i32]),
         "pier_placement_plan": (i32, [i32, ctypes.POINTER(i64), i32, i32, i32, vp,
                                       ctypes.POINTER(i32), ctypes.POINTER(i32)]),
         "pier_bind_replica": (i32, [vp, i32, pp, pp, pp, pp, i32]),
@@ -183,6 +184,10 @@ def pier_ctx_set_launch(ctx, chunk_elems=0, unroll=0, max_grid=0, nontemporal=-1
                                        int(nontemporal)))
 
 
+def pier_ctx_set_offload_writeback(ctx, trailing):
+    _check(_load().pier_ctx_set_offload_writeback(ctx.handle, int(trailing)))
+
+
 def pier_ctx_set_occupancy(ctx, wg_threads=0, lds_bytes=-1):
     _check(_load().pier_ctx_set_occupancy(ctx.handle, int(wg_threads), int(lds_bytes)))
 
@@ -253,7 +258,7 @@ def pier_offload_stream(ctx, *, outer_lr, mu, phase, chunk_bytes, workspace, com
     return stats
 
 
-ABI_VERSION = 1     # PIER_ABI_VERSION of the header this binding was written against
+ABI_VERSION = 2     # PIER_ABI_VERSION of the header this binding was written against
 
 
 def pier_abi_version():

@@ -90,6 +90,7 @@ struct pier_ctx {
     std::map<size_t, OffloadPlan> plans;
     hipEvent_t offload_done = nullptr;  // end of the previous offload call's copy-back
     bool offload_done_valid = false;
+    bool offload_trailing = false;      // compute stream does not wait for the copy-back
 };
 
 namespace {
@@ -591,6 +592,14 @@ pier_status pier_offload_workspace_bytes(const pier_ctx* c, size_t chunk_bytes, 
     return PIER_OK;
 }
 
+pier_status pier_ctx_set_offload_writeback(pier_ctx* c, int trailing)
+{
+    if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
+    if (trailing != 0 && trailing != 1) return fail(PIER_ERR_INVALID_ARG, "trailing = %d: need 0 or 1", trailing);
+    c->offload_trailing = trailing != 0;
+    return PIER_OK;
+}
+
 pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chunk_bytes,
                                 void* workspace, size_t workspace_bytes, void* compute_stream,
                                 void* h2d_stream, void* d2h_stream, pier_offload_stats* stats)
@@ -613,7 +622,7 @@ pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chu
     const size_t piece_bytes = std::min(chunk_bytes, (total + 15) / 16 * 16);
     const int64_t piece_elems = static_cast<int64_t>(piece_bytes / 4);
     const int n_pieces = static_cast<int>((c->N + piece_elems - 1) / piece_elems);
-    const int n_slots = static_cast<int>(std::min<size_t>(std::min<size_t>(4, n_pieces),
+    const int n_slots = static_cast<int>(std::min<size_t>(std::min<size_t>(64, n_pieces),
                                                           workspace_bytes / (2 * piece_bytes)));
     if (n_slots < 1)
         return fail(PIER_ERR_INVALID_ARG, "workspace of %zu bytes holds no staging slot of 2 x %zu bytes",
@@ -695,7 +704,7 @@ pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chu
     }
     PIER_HIP(hipEventRecord(c->offload_done, sout));
     c->offload_done_valid = true;
-    PIER_HIP(hipStreamWaitEvent(sc, c->offload_done, 0));
+    if (!c->offload_trailing) PIER_HIP(hipStreamWaitEvent(sc, c->offload_done, 0));
 
     if (stats) {
         PIER_HIP(hipEventSynchronize(c->offload_done));
@@ -714,6 +723,8 @@ pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chu
         float wall = 0.f;
         PIER_HIP(hipEventElapsedTime(&wall, EV(0, H2D_B), EV(n_pieces - 1, D2H_E)));
         stats->wall_ms = wall;
+        PIER_HIP(hipEventElapsedTime(&wall, EV(0, H2D_B), EV(n_pieces - 1, KER_E)));
+        stats->compute_ms = wall;
     }
     return PIER_OK;
 }

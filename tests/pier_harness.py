@@ -74,6 +74,7 @@ class Run:
         self.hp = hp or dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
         self.seed, self.grad_std = seed, grad_std
         self.offload, self.chunk_bytes = offload, chunk_bytes
+        self.want_stats = True      # False: the offload call returns after enqueueing
         self.stream = stream or torch.cuda.current_stream()
         self.t = 0
         gdt = torch.bfloat16 if grad_bf16 else torch.float32
@@ -231,7 +232,7 @@ class Run:
             self.stats = pier.pier_offload_stream(self.ctx, outer_lr=lr, mu=mu, phase=phase,
                                                   chunk_bytes=self.chunk_bytes, workspace=self.workspace,
                                                   compute_stream=self.stream, h2d_stream=self.s_in,
-                                                  d2h_stream=self.s_out, want_stats=True)
+                                                  d2h_stream=self.s_out, want_stats=self.want_stats)
         else:
             pier.pier_outer_step(self.ctx, outer_lr=lr, mu=mu, phase=phase, stream=self.stream)
         O.outer(self.oP, self.oA, self.oMo, mu=mu, lr=lr, phase=phase)

@@ -324,6 +324,45 @@ def test_offload_is_bit_identical_to_resident(chunk_bytes, phase):
     _log("offload stats pieces=%d slots=%d wall=%.3f ms" % (st.n_pieces, st.n_slots, st.wall_ms))
 
 
+@pytest.mark.parametrize("slots", [2, 9])
+def test_offload_with_trailing_write_back(slots):
+    """Trailing mode: the compute stream does not wait for the copy-back, so the next inner steps
+    are enqueued (and may run) while anchor and M are still on their way to the host; the next
+    offload call orders itself behind the previous copy-back.  Same numbers as the resident step."""
+    import paper_2511_17849_amd as pier
+    H_ = _harness()
+    numels = [300_000, 4096, 4, 0, 1_200_000, 20, 64]
+    chunk = 1 << 19
+    _log("offload, trailing write-back, %d slots" % slots)
+    res = H_.Run(numels, 4, seed=23)
+    off = H_.Run(numels, 4, seed=23, offload=True, chunk_bytes=chunk)
+    off.workspace = torch.empty(2 * chunk * slots, dtype=torch.uint8, device="cuda")
+    off.want_stats = False
+    pier.pier_ctx_set_offload_writeback(off.ctx, 1)
+    with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+        pier.pier_ctx_set_offload_writeback(off.ctx, 2)
+    for r in (res, off):
+        r.inner_steps(2, shared_stream=True)
+        r.outer(mu=0.9, lr=0.0, phase=WARMUP)
+        r.inner_steps(1)
+        r.outer(mu=0.99, lr=0.6, phase=PIER)
+        r.outer(mu=0.95, lr=1.1, phase=PIER)        # back to back: waits for the previous copy-back itself
+        r.inner_steps(1)
+    rep = off.check("trailing")                    # synchronises the device, hence every stream
+    assert rep["bit_exact"], rep
+    a, b = res.device_state(), off.device_state()
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    pier.pier_ctx_set_offload_writeback(off.ctx, 0)
+    off.want_stats = True
+    off.outer(mu=0.9, lr=1.1, phase=PIER)
+    res.outer(mu=0.9, lr=1.1, phase=PIER)
+    assert off.stats.n_slots == min(slots, off.stats.n_pieces) and 0 < off.stats.compute_ms <= off.stats.wall_ms
+    a, b = res.device_state(), off.device_state()
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+
+
 def test_offload_with_odd_sized_tensors():
     """Flat host arrays pack tensors back to back, so odd sizes put later tensors off
     the 16-byte grid: the kernel must take its scalar path there, same numbers."""
