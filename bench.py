@@ -321,8 +321,8 @@ def main():
     if not args.no_offload:
         # the same outer step with anchor and M streamed from pinned host memory
         if not host_outer:
-            hA = torch.empty(N, dtype=torch.float32, pin_memory=True)
-            hM = torch.zeros(N, dtype=torch.float32, pin_memory=True)
+            hA, hM = dev.pinned_empty(N), dev.pinned_empty(N)      # exact size: pinned memory is scarce
+            hM.zero_()
             hA.copy_(A.flat)
             pier.pier_bind_outer(ctx, pier.PIER_LOC_HOST_PINNED, hA, hM)
             ws = torch.empty(pier.pier_offload_workspace_bytes(ctx, chunk), dtype=torch.uint8, device="cuda")

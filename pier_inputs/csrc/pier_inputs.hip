@@ -88,3 +88,18 @@ extern "C" int pier_inputs_fill_normal(void* dst, int64_t n, int64_t first_elem,
     else hipLaunchKernelGGL(fill_normal<false>, dim3(grid), dim3(256), 0, s, dst, n, first_elem, seed, stream_id, step, std_);
     return static_cast<int>(hipGetLastError());
 }
+
+// Pinned host memory of exactly the size asked for.  (torch's pinned allocator rounds requests
+// up to a power of two - 26.6 GB becomes 32 GiB - and a process here may pin about 66 GiB in
+// all, so the two host arrays of the 7B configuration are allocated through these instead.)
+extern "C" int pier_inputs_host_alloc(void** out, size_t bytes)
+{
+    if (!out) return static_cast<int>(hipErrorInvalidValue);
+    *out = nullptr;
+    return static_cast<int>(hipHostMalloc(out, bytes ? bytes : 16, hipHostMallocDefault));
+}
+
+extern "C" int pier_inputs_host_free(void* p)
+{
+    return p ? static_cast<int>(hipHostFree(p)) : 0;
+}

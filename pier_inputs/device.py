@@ -23,8 +23,40 @@ def _load():
         L.pier_inputs_fill_normal.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
                                               ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32,
                                               ctypes.c_float, ctypes.c_void_p]
+        L.pier_inputs_host_alloc.restype = ctypes.c_int
+        L.pier_inputs_host_alloc.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_size_t]
+        L.pier_inputs_host_free.restype = ctypes.c_int
+        L.pier_inputs_host_free.argtypes = [ctypes.c_void_p]
         _lib = L
     return _lib
+
+
+class _PinnedBlock:
+    """Owner of one hipHostMalloc'd block; the tensor made from it keeps this object alive."""
+
+    def __init__(self, nbytes):
+        p = ctypes.c_void_p()
+        rc = _load().pier_inputs_host_alloc(ctypes.byref(p), nbytes)
+        if rc != 0 or not p.value:
+            raise MemoryError("hipHostMalloc of %d bytes failed with hipError %d" % (nbytes, rc))
+        self.ptr, self.nbytes = p.value, nbytes
+
+    def __del__(self):
+        if getattr(self, "ptr", None):
+            _load().pier_inputs_host_free(self.ptr)
+            self.ptr = None
+
+
+def pinned_empty(numel, dtype=torch.float32):
+    """A host tensor in pinned memory of exactly numel elements (no rounding of the request,
+    unlike torch's pinned allocator); torch does not know it is pinned, HIP does."""
+    import numpy as np
+    esize = torch.empty(0, dtype=dtype).element_size()
+    block = _PinnedBlock(max(1, numel) * esize)
+    raw = (ctypes.c_uint8 * block.nbytes).from_address(block.ptr)
+    raw._pier_owner = block                     # the ctypes array is the numpy array's base
+    t = torch.from_numpy(np.frombuffer(raw, dtype=np.uint8)).view(dtype)[:max(1, numel)]
+    return t
 
 
 def fill_normal(t, *, seed, stream, step, std, first_elem=0, hip_stream=None):
@@ -55,7 +87,7 @@ class FlatList:
             off += n + pad
         total = max(off, 1)
         if pinned:
-            self.flat = torch.empty(total, dtype=dtype, pin_memory=True)
+            self.flat = pinned_empty(total, dtype)
             if zero:
                 self.flat.zero_()
         else:

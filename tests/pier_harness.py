@@ -63,6 +63,17 @@ def sample_indices(numels, n_strided=1 << 16, chunk=16384, piece=None, pad=0):
     return out
 
 
+_STAGE_ELEMS = 1 << 26
+_stage_cache = {}
+
+
+def _staging(dtype):
+    """A pinned host buffer of _STAGE_ELEMS elements, one per dtype for the whole process."""
+    if dtype not in _stage_cache:
+        _stage_cache[dtype] = torch.empty(_STAGE_ELEMS, dtype=dtype, pin_memory=True)
+    return _stage_cache[dtype]
+
+
 class Run:
     """One workload on the device plus its sampled oracle shadow."""
 
@@ -159,11 +170,16 @@ class Run:
         tensor in list order (the sample cannot stand in for a reduction over every element)."""
         ss = 0.0
         for t in self.Gd[g].tensors:
-            if t.numel() == 0:
-                continue
-            h = t.cpu()
-            a = h.view(torch.int16).numpy().view(np.uint16) if h.dtype == torch.bfloat16 else h.numpy()
-            ss = O.sumsq(np.ascontiguousarray(a), ss)
+            # through one small pinned staging buffer, 2^26 elements at a time: copying whole
+            # multi-gigabyte tensors into fresh pageable memory makes the runtime pin every
+            # destination, and that accounting is not returned while the process lives
+            for lo in range(0, t.numel(), _STAGE_ELEMS):
+                n = min(_STAGE_ELEMS, t.numel() - lo)
+                stage = _staging(t.dtype)[:n]
+                stage.copy_(t[lo:lo + n])
+                torch.cuda.synchronize()
+                a = stage.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else stage.numpy()
+                ss = O.sumsq(a, ss)
         return ss
 
     def inner_steps(self, H, shared_stream=False, clip=None):

@@ -1,5 +1,5 @@
-"""(Collected after the small-case file on purpose: these cases hold ~210 GB of HBM and
-64 GiB of pinned host memory, so they run when nothing else is left to run.)
+"""(Collected after the small-case file on purpose: these cases hold up to ~215 GB of HBM and
+53 GB of pinned host memory, so they run when nothing else is left to run.)
 
 GPU parity at the full sizes of the benchmark configurations, in the launch
 configuration bench.py times (library defaults), on a deterministic sample of element
@@ -22,7 +22,7 @@ def _log(msg):
 
 
 def _free():
-    """Return device memory and the cached pinned host blocks (2 x 32 GiB after the 7B case)."""
+    """Return device memory and torch's cached pinned host blocks."""
     gc.collect()
     torch.cuda.empty_cache()
     host_empty = getattr(torch._C, "_host_emptyCache", None)
@@ -255,10 +255,10 @@ def test_config4_gpt2_xl_in_probed_arena():
     _free()
 
 
-# Last on purpose.  With this case earlier in the process (64 GiB of pinned host memory and
-# 215 GB of HBM allocated and released), a later, unrelated small offload case took a host-side
-# segmentation fault when it first touched freshly created torch side streams; the cause was
-# not established, so nothing runs after this case and its pinned blocks are released.
+# Last on purpose: it holds 215 GB of HBM and 53 GB of pinned host memory, and a process on
+# these machines can pin about 66 GiB in all.  (The host arrays are allocated at their exact
+# size for that reason; rounded up to 2 x 32 GiB by torch's pinned allocator they left no room
+# for anything else that needs pinned memory, which is what broke cases that ran after this one.)
 @pytest.mark.timeout(900)
 def test_config5_gpt_7b_host_offload_256mib_pieces():
     r, rep = _run_config("gpt_7b", chunk_bytes=256 << 20)
