@@ -104,6 +104,34 @@ def test_config3_gpt2_medium_bf16_gradients():
 
 
 @pytest.mark.timeout(600)
+def test_train_step_at_gpt2_small_size_offloaded():
+    """Twelve iterations of Algorithm 2's loop through pier_train_step at GPT-2 small size (G = 4):
+    scheduled inner learning rate, global-norm clipping (norm 11.2 against threshold 1), bf16
+    working copies, the outer step every third iteration through the host-offload stream with
+    trailing write-back; the oracle mirrors it on the sampled elements and reduces every whole
+    gradient for the norms."""
+    import paper_2511_17849_amd as pier
+    import pier_harness as H_
+    from pier_inputs import shapes
+    w = shapes.workloads()["gpt2_small"]
+    chunk = 32 << 20
+    idx = H_.sample_indices(w.numels, chunk=1024, piece=chunk // 4)
+    _log("train_step at GPT-2 small size: N=%d sampled=%d" % (w.N, idx.size))
+    r = H_.Run(w.numels, 4, seed=12, sample=idx, shadow=True, offload=True, chunk_bytes=chunk)
+    try:
+        r.workspace = torch.empty(2 * chunk * 8, dtype=torch.uint8, device="cuda")
+        pier.pier_ctx_set_offload_writeback(r.ctx, 1)
+        r.train_steps(12, T=60, r=3, lr_max=3e-4, lr_min=3e-5, warmup_frac=0.1, clip=1.0)
+        rep = r.check("train_step, GPT-2 small")
+        _log("train_step at GPT-2 small size: %s syncs %s" % (rep, [(t, ph, mu) for t, ph, mu, _ in r.sync_log]))
+        assert rep["bit_exact"], rep
+        assert [(t, ph) for t, ph, _, _ in r.sync_log] == [(3, WARMUP), (6, WARMUP), (9, PIER), (12, PIER)]
+    finally:
+        del r
+        _free()
+
+
+@pytest.mark.timeout(600)
 def test_sixty_four_groups_at_gpt2_small_size():
     """The paper's largest group count (64) at GPT-2 small shapes: 64 models of 124 M parameters
     (32 GB) through the outer kernel for arbitrary group counts, lazy-start and Pier phases."""
