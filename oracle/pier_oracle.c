@@ -15,8 +15,10 @@
  *
  * Pins (tests/test_oracle_pins.py): step-1 and constant-gradient closed forms,
  * torch.optim.AdamW and torch.optim.SGD(nesterov=True) on CPU as independent
- * library routines, hand-computed Nesterov rounds, warmup telescoping, the
- * schedule constants the paper prints (tests/golden/schedules.txt).
+ * library routines, hand-computed Nesterov rounds, the lazy-start synchronisation
+ * returning the model bit for bit for every group count, its momentum against the
+ * exactly rounded difference and the telescoping sum, the schedule constants the
+ * paper prints (tests/golden/schedules.txt).  Every function here has a pin.
  */
 #include <math.h>
 #include <stdint.h>
@@ -135,22 +137,45 @@ void pier_oracle_to_bf16(const float* x, uint16_t* out, int64_t n)
 }
 
 /* ------------------------------------------------------------------------
- * Outer step (Algorithm 2, the else-branch; Algorithm 1, the t mod r = 0
- * branch).  theta[g] is group g's current model, a the model at the previous
- * synchronisation (theta_{t-r}), M the outer momentum.
+ * Synchronisation in the lazy-start phase (Algorithm 1, the t mod r = 0 branch).
+ * The algorithm is stated for ONE model, trained in ordinary synchronised data
+ * parallelism; the sub-groups only come into being afterwards (Algorithm 2,
+ * second statement).  With theta_t that model and a = theta_{t-r}:
+ *
+ *   delta = theta_t - a
+ *   M <- mu M + delta
+ *   a <- theta_t          (the next synchronisation's theta_{t-r})
+ *
+ * and the model itself is not touched ("only accumulates the momentum without
+ * applying it", section "Momentum Warmup").  A caller that already keeps G
+ * copies of the model in this phase keeps them identical, so the model is read
+ * from copy 0; nothing is averaged, because no sum of G equal floats followed
+ * by a division returns the float itself once G is 3, 5, 6, 7, ...
+ * ---------------------------------------------------------------------- */
+static void lazy_start_sync(const float* model, float* a, float* M, int64_t n, float mu)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        float delta = model[i] - a[i];
+        M[i] = mu * M[i] + delta;
+        a[i] = model[i];
+    }
+}
+
+/* ------------------------------------------------------------------------
+ * Outer step of the Pier phase (Algorithm 2, the else-branch).  theta[g] is
+ * group g's current model, a the model at the previous synchronisation
+ * (theta_{t-r}), M the outer momentum.
  *
  *   delta = mean over groups of (theta_g - a)      [difference, then the
  *                                                   all-reduce, as a mean]
  *   M <- mu M + delta
- *   phase 1 (Pier):   theta <- a + lr (mu M + delta); written to a and to
- *                     every group (all groups hold the same model afterwards)
- *   phase 0 (warmup): momentum only; a <- current model (mean of the
- *                     groups, which are identical in this phase); the groups'
- *                     models are not touched.
+ *   theta <- a + lr (mu M + delta); written to a and to every group (all
+ *   groups hold the same model afterwards)
+ *
  * Summation over groups runs g = 0, 1, ..., G-1.
  * ---------------------------------------------------------------------- */
-void pier_oracle_outer(float* const* theta, int G, float* a, float* M, int64_t n,
-                       float mu, float lr, int phase)
+static void pier_sync(float* const* theta, int G, float* a, float* M, int64_t n,
+                      float mu, float lr)
 {
     float invG = 1.0f / (float)G;
     for (int64_t i = 0; i < n; ++i) {
@@ -159,67 +184,100 @@ void pier_oracle_outer(float* const* theta, int G, float* a, float* M, int64_t n
         float d = s * invG;
         float Mn = mu * M[i] + d;
         M[i] = Mn;
-        if (phase == 1) {
-            float x = a[i] + lr * (mu * Mn + d);
-            a[i] = x;
-            for (int g = 0; g < G; ++g) theta[g][i] = x;
-        } else {
-            float s2 = 0.0f;
-            for (int g = 0; g < G; ++g) s2 = s2 + theta[g][i];
-            a[i] = s2 * invG;
-        }
+        float x = a[i] + lr * (mu * Mn + d);
+        a[i] = x;
+        for (int g = 0; g < G; ++g) theta[g][i] = x;
     }
+}
+
+/* phase 1: Pier's outer step; phase 0: the lazy-start synchronisation (lr unused). */
+void pier_oracle_outer(float* const* theta, int G, float* a, float* M, int64_t n,
+                       float mu, float lr, int phase)
+{
+    if (phase == 1) pier_sync(theta, G, a, M, n, mu, lr);
+    else lazy_start_sync(theta[0], a, M, n, mu);
 }
 
 /* ------------------------------------------------------------------------
  * Schedules.  T = total training iterations, t = current iteration.
- * Breakpoints are compared in integers (10 t vs T, 100 t vs 15 T, ...), so
- * that 0.15 T never goes through a rounded product.
+ *
+ * The paper gives every breakpoint as a share of training: 10 %, 15 %, 20 %,
+ * 80 %.  They are kept here as the fractions 1/10, 3/20, 1/5, 4/5, and "t has
+ * reached the share num/den of T" is decided exactly, by cross-multiplying
+ * integers; 0.15 T is never formed.
  * ---------------------------------------------------------------------- */
+typedef struct { int64_t num, den; } share;
+static const share k10pct = {1, 10}, k15pct = {3, 20}, k20pct = {1, 5}, k80pct = {4, 5};
+
+/* t/T >= num/den ? */
+static int reached(int64_t t, int64_t T, share s)
+{
+    return t * s.den >= s.num * T;
+}
+
+/* t/T > num/den ? */
+static int passed(int64_t t, int64_t T, share s)
+{
+    return t * s.den > s.num * T;
+}
 
 /* Lazy-start phase covers the first 10% (section "Momentum Decay"):
  * iterations 1..0.1T accumulate momentum only (Algorithm 1's loop bound is
- * inclusive); the first applied outer step is the first one after 0.1T. */
+ * inclusive, so t/T = 1/10 itself still belongs to it); the first applied outer
+ * step is the first one after 0.1T. */
 int pier_oracle_phase(int64_t t, int64_t T)
 {
-    return (10 * t <= T) ? 0 : 1;
+    return passed(t, T, k10pct) ? 1 : 0;
 }
 
-/* Algorithm 2's three-way choice, literally: 0.99 on [0.1T, 0.15T), 0.95 on
- * [0.15T, 0.2T), 0.9 otherwise.  (Below 0.1T that "otherwise" equals the
- * warmup default of 0.9 given with Algorithm 1.) */
+/* Algorithm 2's three-way choice: 0.99 on [10%, 15%), 0.95 on [15%, 20%), 0.9
+ * otherwise.  (Below 10% that "otherwise" equals the warmup default of 0.9 given
+ * with Algorithm 1.)  Walked from the last band to the first. */
 float pier_oracle_mu(int64_t t, int64_t T)
 {
-    if (10 * t >= T && 100 * t < 15 * T) return 0.99f;
-    if (100 * t >= 15 * T && 10 * t < 2 * T) return 0.95f;
+    if (reached(t, T, k20pct)) return 0.9f;
+    if (reached(t, T, k15pct)) return 0.95f;
+    if (reached(t, T, k10pct)) return 0.99f;
     return 0.9f;
 }
 
 /* Outer learning rate (section "Implementation"): linear from 0 to 1 between
  * 10% and 20% of training, 1.1 from 20% to 80%, 0.9 for the last 20%.
- * Before 10% no outer step is applied; 0 is returned there. */
+ * Before 10% no outer step is applied; 0 is returned there.  On the ramp the
+ * value is (t - T/10) / (T/5 - T/10) = (10 t - T) / T, an exact ratio of
+ * integers rounded once to double and once to fp32. */
 float pier_oracle_outer_lr(int64_t t, int64_t T)
 {
-    if (10 * t < T) return 0.0f;
-    if (10 * t < 2 * T) return (float)((double)(10 * t - T) / (double)T);
-    if (10 * t < 8 * T) return 1.1f;
-    return 0.9f;
+    if (reached(t, T, k80pct)) return 0.9f;
+    if (reached(t, T, k20pct)) return 1.1f;
+    if (!reached(t, T, k10pct)) return 0.0f;
+    int64_t above = 10 * t - T;            /* ten times the distance from the 10% mark */
+    return (float)((double)above / (double)T);
 }
 
 /* Inner learning rate (Table I: cosine decay style, learning rate warmup proportion 2%,
- * a minimum learning rate, decay iterations = training iterations): linear from 0 to
- * lr_max over the first warmup_frac * T iterations (iteration t uses lr_max * t / W,
- * W = warmup_frac * T), then half a cosine from lr_max at t = W down to lr_min at
- * t = T.  Evaluated in double, rounded once to fp32. */
-float pier_oracle_inner_lr(int64_t t, int64_t T, float lr_max, float lr_min, double warmup_frac)
+ * a minimum learning rate, decay iterations = training iterations).  Two legs:
+ *   warmup, t <= W = warmup_frac T:  the share t / W of lr_max (so iteration 1 already
+ *                                    moves, and t = W uses lr_max itself);
+ *   decay,  W < t < T:               lr_min plus the share (1 + cos(pi x)) / 2 of the span
+ *                                    lr_max - lr_min, x = (t - W) / (T - W) the progress
+ *                                    through the decay leg; lr_min from T on.
+ * Evaluated in double, rounded once to fp32. */
+static double cosine_share(double progress)
 {
     const double pi = 3.14159265358979323846;
+    return 0.5 * (cos(pi * progress) + 1.0);
+}
+
+float pier_oracle_inner_lr(int64_t t, int64_t T, float lr_max, float lr_min, double warmup_frac)
+{
+    double hi = (double)lr_max, lo = (double)lr_min;
     double W = warmup_frac * (double)T;
-    if (W > 0.0 && (double)t <= W) return (float)((double)lr_max * (double)t / W);
+    int in_warmup = W > 0.0 && (double)t <= W;
+    if (in_warmup) return (float)(hi * (double)t / W);
     if (t >= T) return lr_min;
-    double ratio = ((double)t - W) / ((double)T - W);
-    double coeff = 0.5 * (cos(pi * ratio) + 1.0);
-    return (float)((double)lr_min + coeff * ((double)lr_max - (double)lr_min));
+    double progress = ((double)t - W) / ((double)T - W);
+    return (float)(lo + cosine_share(progress) * (hi - lo));
 }
 
 /* The momentum coefficient and rate one synchronisation at iteration t uses:

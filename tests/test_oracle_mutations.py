@@ -39,10 +39,10 @@ MUTATIONS = [
     ("bf16: truncation instead of rounding", "out[i] = (uint16_t)((b + 0x7FFFu + lsb) >> 16);", "out[i] = (uint16_t)(b >> 16);"),
     ("bf16: ties away from zero", "out[i] = (uint16_t)((b + 0x7FFFu + lsb) >> 16);", "out[i] = (uint16_t)((b + 0x8000u) >> 16);"),
     ("bf16: NaN not quieted", "if ((b & 0x7FFFFFFFu) > 0x7F800000u) { out[i] = 0x7FC0; continue; }", ""),
-    ("inner lr: cosine over T instead of T - W", "double ratio = ((double)t - W) / ((double)T - W);", "double ratio = ((double)t - W) / ((double)T);"),
-    ("inner lr: warmup from lr_min", "return (float)((double)lr_max * (double)t / W);", "return (float)((double)lr_min + ((double)lr_max - lr_min) * (double)t / W);"),
-    ("inner lr: full cosine period", "cos(pi * ratio)", "cos(2.0 * pi * ratio)"),
-    ("inner lr: decays to zero", "(float)((double)lr_min + coeff * ((double)lr_max - (double)lr_min))", "(float)(coeff * (double)lr_max)"),
+    ("inner lr: cosine over T instead of T - W", "double progress = ((double)t - W) / ((double)T - W);", "double progress = ((double)t - W) / ((double)T);"),
+    ("inner lr: warmup from lr_min", "return (float)(hi * (double)t / W);", "return (float)(lo + (hi - lo) * (double)t / W);"),
+    ("inner lr: full cosine period", "cos(pi * progress)", "cos(2.0 * pi * progress)"),
+    ("inner lr: decays to zero", "(float)(lo + cosine_share(progress) * (hi - lo))", "(float)(cosine_share(progress) * hi)"),
     ("sum instead of mean", "float d = s * invG;", "float d = s;"),
     ("anchor minus model", "s = s + (theta[g][i] - a[i]);", "s = s + (a[i] - theta[g][i]);"),
     ("first group only", "for (int g = 0; g < G; ++g) s = s + (theta[g][i] - a[i]);",
@@ -50,19 +50,34 @@ MUTATIONS = [
     ("momentum without mu", "float Mn = mu * M[i] + d;", "float Mn = M[i] + d;"),
     ("heavy ball, no Nesterov term", "lr * (mu * Mn + d)", "lr * Mn"),
     ("look-ahead uses the old momentum",
-     "M[i] = Mn;\n        if (phase == 1) {\n            float x = a[i] + lr * (mu * Mn + d);",
-     "float Mold = M[i]; M[i] = Mn;\n        if (phase == 1) {\n            float x = a[i] + lr * (mu * Mold + d);"),
+     "M[i] = Mn;\n        float x = a[i] + lr * (mu * Mn + d);",
+     "float Mold = M[i]; M[i] = Mn;\n        float x = a[i] + lr * (mu * Mold + d);"),
     ("lr on the gradient only", "a[i] + lr * (mu * Mn + d)", "a[i] + (mu * Mn + lr * d)"),
     ("momentum not stored", "M[i] = Mn;", ""),
     ("groups not re-synchronised", "for (int g = 0; g < G; ++g) theta[g][i] = x;", "theta[0][i] = x;"),
     ("anchor not advanced", "a[i] = x;", ""),
-    ("warmup applies the step", "if (phase == 1) {", "if (phase == 1 || phase == 0) {"),
-    ("warmup keeps the old anchor", "a[i] = s2 * invG;", ""),
+    ("warmup applies the step", "if (phase == 1) pier_sync", "if (phase == 1 || phase == 0) pier_sync"),
+    ("warmup keeps the old anchor", "a[i] = model[i];", ""),
+    ("warmup anchor is the fp32 mean of the copies (3 theta / 3 is not theta)",
+     "else lazy_start_sync(theta[0], a, M, n, mu);",
+     "else { lazy_start_sync(theta[0], a, M, n, mu);"
+     " for (int64_t i = 0; i < n; ++i) { float s2 = 0.0f; for (int g = 0; g < G; ++g) s2 = s2 + theta[g][i];"
+     " a[i] = s2 * (1.0f / (float)G); } }"),
+    ("warmup difference averaged over the copies",
+     "float delta = model[i] - a[i];\n        M[i] = mu * M[i] + delta;",
+     "float delta = ((model[i] - a[i]) + (model[i] - a[i]) + (model[i] - a[i])) * (1.0f / 3.0f);\n        M[i] = mu * M[i] + delta;"),
+    ("warmup difference with the wrong sign", "float delta = model[i] - a[i];", "float delta = a[i] - model[i];"),
+    ("warmup momentum without mu", "M[i] = mu * M[i] + delta;", "M[i] = M[i] + delta;"),
+    ("warmup momentum overwritten, not accumulated", "M[i] = mu * M[i] + delta;", "M[i] = delta;"),
+    ("warmup writes the model", "a[i] = model[i];", "a[i] = model[i]; ((float*)model)[i] = a[i] + delta;"),
     ("mu bands swapped", "return 0.99f;", "return 0.95f;"),
-    ("mu boundary at 15% closed on the wrong side", "100 * t < 15 * T) return 0.99f", "100 * t <= 15 * T) return 0.99f"),
-    ("lr plateau values swapped", "if (10 * t < 8 * T) return 1.1f;\n    return 0.9f;", "if (10 * t < 8 * T) return 0.9f;\n    return 1.1f;"),
-    ("lr ramp from 0.1 T as fraction of T", "(double)(10 * t - T) / (double)T", "(double)(10 * t - T) / (double)(10 * T)"),
-    ("lazy start ends one step early", "return (10 * t <= T) ? 0 : 1;", "return (10 * t < T) ? 0 : 1;"),
+    ("mu boundary at 15% closed on the wrong side", "if (reached(t, T, k15pct)) return 0.95f;", "if (passed(t, T, k15pct)) return 0.95f;"),
+    ("mu: 15% typed as 3/25", "k15pct = {3, 20}", "k15pct = {3, 25}"),
+    ("lr plateau values swapped", "if (reached(t, T, k80pct)) return 0.9f;\n    if (reached(t, T, k20pct)) return 1.1f;",
+     "if (reached(t, T, k80pct)) return 1.1f;\n    if (reached(t, T, k20pct)) return 0.9f;"),
+    ("lr ramp from 0.1 T as fraction of T", "(double)above / (double)T", "(double)above / (double)(10 * T)"),
+    ("lr ramp measured from 0", "int64_t above = 10 * t - T;", "int64_t above = 10 * t;"),
+    ("lazy start ends one step early", "return passed(t, T, k10pct) ? 1 : 0;", "return reached(t, T, k10pct) ? 1 : 0;"),
     ("warmup mu taken from the decay schedule", "if (*phase == 0) { *mu = 0.9f; *lr = 0.0f; }",
      "if (*phase == 0) { *mu = pier_oracle_mu(t, T); *lr = 0.0f; }"),
 ]
@@ -81,9 +96,12 @@ def battery():
         (pins.test_clip_matches_torch_clip_grad_norm, ()),
         (pins.test_outer_single_group_unit_rate_returns_the_model, ()),
         (pins.test_outer_unit_rate_no_momentum_is_the_replica_mean, ()),
+        (pins.test_lazy_start_sync_returns_the_model_bit_for_bit, (1,)),
+        (pins.test_lazy_start_sync_returns_the_model_bit_for_bit, (3,)),
+        (pins.test_lazy_start_sync_returns_the_model_bit_for_bit, (8,)),
         (pins.test_outer_nesterov_two_rounds_by_hand, ()),
         (pins.test_outer_matches_torch_sgd_nesterov, ()),
-        (pins.test_warmup_accumulates_without_touching_the_model, ()),
+        (pins.test_warmup_accumulates_without_touching_the_model, (3,)),
         (pins.test_rounds_against_torch_optimizers, ()),
     ]
     calls += [(pins.test_schedules_match_the_printed_constants, (row,)) for row in pins._golden_rows()]

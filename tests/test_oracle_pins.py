@@ -309,11 +309,41 @@ def test_outer_unit_rate_no_momentum_is_the_replica_mean():
     for x in t:
         assert np.array_equal(x, a)                        # every group re-synchronised
     np.testing.assert_allclose(M, mean - a0, rtol=0, atol=1e-9)
-    # identical replicas, power-of-two G: the warmup anchor is bitwise the model
-    same = [ths[0].copy() for _ in range(G)]
-    a = a0.copy()
-    O.outer(same, a, np.zeros(n, np.float32), mu=0.9, lr=0.0, phase=O.WARMUP)
-    assert np.array_equal(a, ths[0])
+
+
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 8, 16, 64])
+def test_lazy_start_sync_returns_the_model_bit_for_bit(G):
+    """Algorithm 1 works on one model: after a synchronisation the stored theta_{t-r} IS theta_t,
+    whatever the number of (identical) copies a caller keeps, and M <- mu M + (theta_t - theta_{t-r}).
+    One fp32 subtraction is the exactly rounded difference, and with mu a power of two mu M is
+    exact, so double arithmetic rounded once gives the fp32 result bit for bit."""
+    rng = np.random.default_rng(60 + G)
+    n = 4096
+    a0 = f32(rng.normal(0, 0.02, n))
+    th = f32(a0 + rng.normal(0, 1e-3, n))
+    th[:7] = [0.0, -0.0, 1e-30, -3.0, 1e3, a0[5], -a0[6]]
+    M0 = f32(rng.normal(0, 1e-3, n))
+    reps = [th.copy() for _ in range(G)]
+    # first synchronisation, M = 0
+    a, M = a0.copy(), np.zeros(n, np.float32)
+    O.outer(reps, a, M, mu=0.9, lr=55.0, phase=O.WARMUP)
+    assert np.array_equal(a.view(np.uint32), th.view(np.uint32))           # signed zeros included
+    assert all(np.array_equal(r.view(np.uint32), th.view(np.uint32)) for r in reps)
+    exact = (th.astype(np.float64) - a0.astype(np.float64)).astype(np.float32)
+    assert np.array_equal(M, exact)
+    # mu = 1/2: mu M is exact, the sum of two floats is exact in double
+    a, M = a0.copy(), M0.copy()
+    O.outer(reps, a, M, mu=0.5, lr=0.0, phase=O.WARMUP)
+    want = (0.5 * M0.astype(np.float64) + exact.astype(np.float64)).astype(np.float32)
+    assert np.array_equal(M, want) and np.array_equal(a, th)
+    # the number of copies does not enter the result
+    a1, M1 = a0.copy(), M0.copy()
+    O.outer([th.copy()], a1, M1, mu=0.9, lr=0.0, phase=O.WARMUP)
+    aG, MG = a0.copy(), M0.copy()
+    O.outer(reps, aG, MG, mu=0.9, lr=0.0, phase=O.WARMUP)
+    assert np.array_equal(a1, aG) and np.array_equal(M1, MG)
+    ref = 0.9 * M0.astype(np.float64) + (th.astype(np.float64) - a0)
+    np.testing.assert_allclose(MG, ref, rtol=2e-7, atol=2e-10)
 
 
 def test_outer_nesterov_two_rounds_by_hand():
@@ -358,9 +388,10 @@ def test_outer_matches_torch_sgd_nesterov():
             assert np.array_equal(x, a)
 
 
-def test_warmup_accumulates_without_touching_the_model():
+@pytest.mark.parametrize("G", [2, 3, 8])
+def test_warmup_accumulates_without_touching_the_model(G):
     rng = np.random.default_rng(9)
-    n, G, K = 300, 2, 5
+    n, K = 300, 5
     th = rng.normal(0, 0.02, n).astype(np.float32)
     a, M, M1 = th.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
     a1 = th.copy()
