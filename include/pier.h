@@ -155,12 +155,18 @@ pier_status pier_grad_norm_last(pier_ctx* ctx, int replica, double* norm_out, fl
                                 void* hip_stream);
 
 /* ----------------------------------------------------------- outer step
- * Algorithm 2's synchronisation branch (PIER) and Algorithm 1's (WARMUP), fused
- * into one kernel over all replicas, with anchor and M on the device:
+ * One kernel launch, with anchor and M on the device.
+ *   PIER (Algorithm 2's synchronisation branch), over all replicas:
  *     delta = (1/G) sum_g (theta_g - anchor)          [the all-reduce's arithmetic]
  *     M     = mu M + delta
- *   PIER:   theta = anchor + outer_lr (mu M + delta); anchor = theta_g = theta for all g
- *   WARMUP: anchor = (1/G) sum_g theta_g; replicas untouched; outer_lr ignored
+ *     theta = anchor + outer_lr (mu M + delta); anchor = theta_g = theta for all g
+ *     (8G + 16 bytes per parameter)
+ *   WARMUP (Algorithm 1's, the lazy-start phase).  That algorithm has ONE model - the
+ *     groups are formed after it - so the model is read from replica 0; the caller
+ *     keeps the replicas identical in this phase (synchronised data parallelism):
+ *     delta = theta_0 - anchor;  M = mu M + delta;  anchor = theta_0  (bit for bit)
+ *     replicas and their AdamW state untouched; outer_lr ignored
+ *     (20 bytes per parameter whatever G)
  * M holds the paper's sign (it accumulates new - old).  Needs every replica bound
  * and pier_bind_outer(PIER_LOC_DEVICE). */
 typedef enum { PIER_PHASE_WARMUP = 0, PIER_PHASE_PIER = 1 } pier_phase;

@@ -21,6 +21,9 @@
 // the expression.
 #include "pier_internal.h"
 
+#include <cstddef>
+#include <type_traits>
+
 namespace pier {
 
 typedef float vfloat4 __attribute__((ext_vector_type(4)));
@@ -423,11 +426,9 @@ hipError_t launch_grad_norm(const Chunk* chunks, int n_chunks, const RepPtrs* ta
 //
 // Algorithm 2, synchronisation branch, for one element held by G groups:
 //   delta = (1/G) sum_g (theta_g - anchor);  M = mu M + delta;
-//   Pier:   theta = anchor + lr (mu M + delta), written to the anchor and to all groups;
-//   warmup: (Algorithm 1) momentum only; the anchor takes the current model, which
-//           is the mean of the (identical) groups; groups untouched.
+//   theta = anchor + lr (mu M + delta), written to the anchor and to all groups.
 // The sum over groups runs g = 0 .. G-1 in that order.
-template <int G, bool PIER>
+template <int G>
 __device__ __forceinline__ void outer_elem(float (&th)[G], float& a, float& M, float mu, float lr,
                                            float invG)
 {
@@ -438,20 +439,13 @@ __device__ __forceinline__ void outer_elem(float (&th)[G], float& a, float& M, f
     const float d = s * invG;
     const float Mn = mu * M + d;
     M = Mn;
-    if constexpr (PIER) {
-        const float x = a + lr * (mu * Mn + d);
-        a = x;
+    const float x = a + lr * (mu * Mn + d);
+    a = x;
 #pragma unroll
-        for (int g = 0; g < G; ++g) th[g] = x;
-    } else {
-        float s2 = 0.0f;
-#pragma unroll
-        for (int g = 0; g < G; ++g) s2 = s2 + th[g];
-        a = s2 * invG;
-    }
+    for (int g = 0; g < G; ++g) th[g] = x;
 }
 
-template <int G, bool PIER>
+template <int G>
 __device__ __forceinline__ void outer_vec(vfloat4 (&TH)[G], vfloat4& A, vfloat4& M, float mu,
                                           float lr, float invG)
 {
@@ -461,17 +455,15 @@ __device__ __forceinline__ void outer_vec(vfloat4 (&TH)[G], vfloat4& A, vfloat4&
 #pragma unroll
         for (int g = 0; g < G; ++g) th[g] = TH[g][k];
         float a = A[k], mm = M[k];
-        outer_elem<G, PIER>(th, a, mm, mu, lr, invG);
+        outer_elem<G>(th, a, mm, mu, lr, invG);
         A[k] = a;
         M[k] = mm;
-        if constexpr (PIER) {
 #pragma unroll
-            for (int g = 0; g < G; ++g) TH[g][k] = th[g];
-        }
+        for (int g = 0; g < G; ++g) TH[g][k] = th[g];
     }
 }
 
-template <int G, bool PIER, bool SHADOW>
+template <int G, bool SHADOW>
 __device__ __forceinline__ void outer_scalar(float* const (&th)[G], unsigned short* const (&wb)[G],
                                              float* a, float* M, int i, float mu, float lr, float invG)
 {
@@ -479,17 +471,15 @@ __device__ __forceinline__ void outer_scalar(float* const (&th)[G], unsigned sho
 #pragma unroll
     for (int g = 0; g < G; ++g) t[g] = ld<false>(th[g] + i);
     float av = ld<false>(a + i), mv = ld<false>(M + i);
-    outer_elem<G, PIER>(t, av, mv, mu, lr, invG);
+    outer_elem<G>(t, av, mv, mu, lr, invG);
     st<false>(a + i, av);
     st<false>(M + i, mv);
-    if constexpr (PIER) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) st<false>(th[g] + i, t[g]);
-        if constexpr (SHADOW) {
-            const unsigned short h = f32_to_bf16(av);       // theta_g == new anchor for every g
+    for (int g = 0; g < G; ++g) st<false>(th[g] + i, t[g]);
+    if constexpr (SHADOW) {
+        const unsigned short h = f32_to_bf16(av);       // theta_g == new anchor for every g
 #pragma unroll
-            for (int g = 0; g < G; ++g) st<false>(wb[g] + i, h);
-        }
+        for (int g = 0; g < G; ++g) st<false>(wb[g] + i, h);
     }
 }
 
@@ -516,13 +506,11 @@ struct OuterRow {
 
 // The tables are separate const __restrict__ parameters: only then may the compiler
 // read them through the scalar unit (they are never written by a kernel).
-template <int WG, int G, int UNROLL, bool FLAT, bool PIER, bool NT, bool SHADOW>
+template <int WG, int G, int UNROLL, bool FLAT, bool NT, bool SHADOW>
 __global__ __launch_bounds__(WG) void outer_kernel(const Chunk* __restrict__ chunks,
                                                    const OuterRow<G>* __restrict__ rows,
                                                    OuterArgs A)
 {
-    static_assert(sizeof(OuterRow<G>) == (kOuterRowHead + 2 * G) * 8, "row layout");
-    static_assert(PIER || !SHADOW, "the lazy-start phase does not touch the replicas");
     const Team<WG> team;
     const int tid = team.lane;
     constexpr int kTile = kBlock * UNROLL;
@@ -569,13 +557,11 @@ __global__ __launch_bounds__(WG) void outer_kernel(const Chunk* __restrict__ chu
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
                     const unsigned o = static_cast<unsigned>(base + u * kBlock + tid) * 16u;
-                    outer_vec<G, PIER>(TH[u], Av[u], Mv[u], A.mu, A.lr, A.invG);
+                    outer_vec<G>(TH[u], Av[u], Mv[u], A.mu, A.lr, A.invG);
                     sto<NT>(a, o, Av[u]);
                     sto<NT>(M, o, Mv[u]);
-                    if constexpr (PIER) {
 #pragma unroll
-                        for (int g = 0; g < G; ++g) sto<NT>(th[g], o, TH[u][g]);
-                    }
+                    for (int g = 0; g < G; ++g) sto<NT>(th[g], o, TH[u][g]);
                     if constexpr (SHADOW) {
                         const vushort4 h = f32_to_bf16(Av[u]);
 #pragma unroll
@@ -588,13 +574,11 @@ __global__ __launch_bounds__(WG) void outer_kernel(const Chunk* __restrict__ chu
                 vfloat4 TH[G], Av = ldo<NT, vfloat4>(a, o), Mv = ldo<NT, vfloat4>(M, o);
 #pragma unroll
                 for (int g = 0; g < G; ++g) TH[g] = ldo<NT, vfloat4>(th[g], o);
-                outer_vec<G, PIER>(TH, Av, Mv, A.mu, A.lr, A.invG);
+                outer_vec<G>(TH, Av, Mv, A.mu, A.lr, A.invG);
                 sto<NT>(a, o, Av);
                 sto<NT>(M, o, Mv);
-                if constexpr (PIER) {
 #pragma unroll
-                    for (int g = 0; g < G; ++g) sto<NT>(th[g], o, TH[g]);
-                }
+                for (int g = 0; g < G; ++g) sto<NT>(th[g], o, TH[g]);
                 if constexpr (SHADOW) {
                     const vushort4 h = f32_to_bf16(Av);
 #pragma unroll
@@ -602,10 +586,10 @@ __global__ __launch_bounds__(WG) void outer_kernel(const Chunk* __restrict__ chu
                 }
             }
             const int i = (n4 << 2) + tid;
-            if (i < len) outer_scalar<G, PIER, SHADOW>(th, wb, a, M, i, A.mu, A.lr, A.invG);
+            if (i < len) outer_scalar<G, SHADOW>(th, wb, a, M, i, A.mu, A.lr, A.invG);
         } else {
             for (int i = tid; i < len; i += kBlock)
-                outer_scalar<G, PIER, SHADOW>(th, wb, a, M, i, A.mu, A.lr, A.invG);
+                outer_scalar<G, SHADOW>(th, wb, a, M, i, A.mu, A.lr, A.invG);
         }
     }
 }
@@ -615,37 +599,31 @@ __global__ __launch_bounds__(WG) void outer_kernel(const Chunk* __restrict__ chu
 // tensor in word 3 of the row: bit 0 for the theta pointers, bit 1 for the working copies),
 // lanes move 128-bit vectors and keep up to eight replica loads in flight; otherwise one
 // element per lane.  Covers the group counts without a specialised kernel.
-template <bool PIER>
 __device__ __forceinline__ void outer_anyG_scalar(const uint64_t* __restrict__ row, const OuterArgs& A,
                                                   float* a, float* M, int64_t off, int i)
 {
 #pragma clang fp contract(off)
     const float av = ld<false>(a + i);
-    float s = 0.0f, s2 = 0.0f;
+    float s = 0.0f;
     for (int g = 0; g < A.G; ++g) {
         const float t = ld<false>(reinterpret_cast<const float*>(row[kOuterRowHead + g]) + off + i);
         s = s + (t - av);
-        s2 = s2 + t;
     }
     const float d = s * A.invG;
     const float Mn = A.mu * ld<false>(M + i) + d;
     st<false>(M + i, Mn);
-    if constexpr (PIER) {
-        const float x = av + A.lr * (A.mu * Mn + d);
-        st<false>(a + i, x);
+    const float x = av + A.lr * (A.mu * Mn + d);
+    st<false>(a + i, x);
+    for (int g = 0; g < A.G; ++g)
+        st<false>(reinterpret_cast<float*>(row[kOuterRowHead + g]) + off + i, x);
+    if (A.shadow) {
+        const unsigned short h = f32_to_bf16(x);
         for (int g = 0; g < A.G; ++g)
-            st<false>(reinterpret_cast<float*>(row[kOuterRowHead + g]) + off + i, x);
-        if (A.shadow) {
-            const unsigned short h = f32_to_bf16(x);
-            for (int g = 0; g < A.G; ++g)
-                st<false>(reinterpret_cast<unsigned short*>(row[kOuterRowHead + A.G + g]) + off + i, h);
-        }
-    } else {
-        st<false>(a + i, s2 * A.invG);
+            st<false>(reinterpret_cast<unsigned short*>(row[kOuterRowHead + A.G + g]) + off + i, h);
     }
 }
 
-template <int WG, bool FLAT, bool PIER, bool NT>
+template <int WG, bool FLAT, bool NT>
 __global__ __launch_bounds__(WG) void outer_kernel_anyG(const Chunk* __restrict__ chunks,
                                                         const uint64_t* __restrict__ rows,
                                                         OuterArgs A)
@@ -676,7 +654,7 @@ __global__ __launch_bounds__(WG) void outer_kernel_anyG(const Chunk* __restrict_
             for (int j = tid; j < n4; j += kBlock) {
                 const unsigned o = static_cast<unsigned>(j) * 16u;
                 vfloat4 Av = ldo<NT, vfloat4>(a, o), Mv = ldo<NT, vfloat4>(M, o);
-                vfloat4 s = {0.0f, 0.0f, 0.0f, 0.0f}, s2 = {0.0f, 0.0f, 0.0f, 0.0f};
+                vfloat4 s = {0.0f, 0.0f, 0.0f, 0.0f};
                 for (int g0 = 0; g0 < A.G; g0 += kBatch) {
                     vfloat4 T[kBatch];
 #pragma unroll
@@ -685,32 +663,83 @@ __global__ __launch_bounds__(WG) void outer_kernel_anyG(const Chunk* __restrict_
                             T[k] = ldo<NT, vfloat4>(reinterpret_cast<const float*>(row[kOuterRowHead + g0 + k]) + ch.off, o);
 #pragma unroll
                     for (int k = 0; k < kBatch; ++k)
-                        if (g0 + k < A.G) {
-                            s = s + (T[k] - Av);
-                            s2 = s2 + T[k];
-                        }
+                        if (g0 + k < A.G) s = s + (T[k] - Av);
                 }
                 const vfloat4 d = s * A.invG;
                 const vfloat4 Mn = A.mu * Mv + d;
                 sto<NT>(M, o, Mn);
-                if constexpr (PIER) {
-                    const vfloat4 x = Av + A.lr * (A.mu * Mn + d);
-                    sto<NT>(a, o, x);
+                const vfloat4 x = Av + A.lr * (A.mu * Mn + d);
+                sto<NT>(a, o, x);
+                for (int g = 0; g < A.G; ++g)
+                    sto<NT>(reinterpret_cast<float*>(row[kOuterRowHead + g]) + ch.off, o, x);
+                if (A.shadow) {
+                    const vushort4 h = f32_to_bf16(x);
                     for (int g = 0; g < A.G; ++g)
-                        sto<NT>(reinterpret_cast<float*>(row[kOuterRowHead + g]) + ch.off, o, x);
-                    if (A.shadow) {
-                        const vushort4 h = f32_to_bf16(x);
-                        for (int g = 0; g < A.G; ++g)
-                            sto<NT>(reinterpret_cast<unsigned short*>(row[kOuterRowHead + A.G + g]) + ch.off, o >> 1, h);
-                    }
-                } else {
-                    sto<NT>(a, o, s2 * A.invG);
+                        sto<NT>(reinterpret_cast<unsigned short*>(row[kOuterRowHead + A.G + g]) + ch.off, o >> 1, h);
                 }
             }
             const int i = (n4 << 2) + tid;      // up to three elements past the last whole vector
-            if (i < ch.len) outer_anyG_scalar<PIER>(row, A, a, M, ch.off, i);
+            if (i < ch.len) outer_anyG_scalar(row, A, a, M, ch.off, i);
         } else {
-            for (int i = tid; i < ch.len; i += kBlock) outer_anyG_scalar<PIER>(row, A, a, M, ch.off, i);
+            for (int i = tid; i < ch.len; i += kBlock) outer_anyG_scalar(row, A, a, M, ch.off, i);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ lazy-start synchronisation
+//
+// Algorithm 1, the t mod r = 0 branch, for one element.  The algorithm is stated for one
+// model (groups are formed only after the warmup), so the model is read from replica 0
+// and nothing is averaged:
+//   delta = theta - anchor;  M = mu M + delta;  anchor = theta.
+// The model, its other replicas and their AdamW state are not touched.  Three streams
+// read, two written: 20 bytes per parameter whatever the group count.
+__device__ __forceinline__ void lazy_start_scalar(const float* th, float* a, float* M, int i, float mu)
+{
+#pragma clang fp contract(off)
+    const float t = ld<false>(th + i);
+    const float d = t - ld<false>(a + i);
+    st<false>(M + i, mu * ld<false>(M + i) + d);
+    st<false>(a + i, t);
+}
+
+template <int WG, bool FLAT, bool NT>
+__global__ __launch_bounds__(WG) void lazy_start_kernel(const Chunk* __restrict__ chunks,
+                                                        const uint64_t* __restrict__ rows,
+                                                        OuterArgs A)
+{
+#pragma clang fp contract(off)
+    const Team<WG> team;
+    const int tid = team.lane;
+    for (int c = team.first; c < A.n_chunks; c += team.stride) {
+        const Chunk ch = chunks[c];
+        const uint64_t* __restrict__ row = rows + static_cast<int64_t>(ch.tensor) * (kOuterRowHead + 2 * A.G);
+        float* __restrict__ a;
+        float* __restrict__ M;
+        if constexpr (FLAT) {
+            const int64_t e = static_cast<int64_t>(row[2]) + ch.off - A.flat_lo;
+            a = A.flat_a + e;
+            M = A.flat_M + e;
+        } else {
+            a = reinterpret_cast<float*>(row[0]) + ch.off;
+            M = reinterpret_cast<float*>(row[1]) + ch.off;
+        }
+        const float* __restrict__ th = reinterpret_cast<const float*>(row[kOuterRowHead]) + ch.off;
+        const uintptr_t mis = (reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(M) |
+                               reinterpret_cast<uintptr_t>(th)) & 15u;
+        if (mis == 0) {
+            const int n4 = ch.len >> 2;
+            for (int j = tid; j < n4; j += kBlock) {
+                const unsigned o = static_cast<unsigned>(j) * 16u;
+                const vfloat4 T = ldo<NT, vfloat4>(th, o), Av = ldo<NT, vfloat4>(a, o), Mv = ldo<NT, vfloat4>(M, o);
+                const vfloat4 d = T - Av;
+                sto<NT>(M, o, A.mu * Mv + d);
+                sto<NT>(a, o, T);
+            }
+            const int i = (n4 << 2) + tid;      // up to three elements past the last whole vector
+            if (i < ch.len) lazy_start_scalar(th, a, M, i, A.mu);
+        } else {
+            for (int i = tid; i < ch.len; i += kBlock) lazy_start_scalar(th, a, M, i, A.mu);
         }
     }
 }
@@ -720,70 +749,83 @@ struct OuterTables {
     const uint64_t* rows;
 };
 
-template <int WG, int G, int U, bool FLAT, bool PIER, bool SHADOW>
+// The uint64 table rows are handed to the register-array kernel as OuterRow<G>: same words,
+// same order (the static_asserts below pin the layout the host writes).
+template <int G>
+static const OuterRow<G>* typed_rows(const uint64_t* rows)
+{
+    static_assert(std::is_standard_layout<OuterRow<G>>::value, "row must be plain data");
+    static_assert(offsetof(OuterRow<G>, a) == 0 && offsetof(OuterRow<G>, M) == 8 &&
+                  offsetof(OuterRow<G>, flat_start) == 16 && offsetof(OuterRow<G>, flags) == 24 &&
+                  offsetof(OuterRow<G>, th) == 8 * kOuterRowHead &&
+                  offsetof(OuterRow<G>, wb) == 8 * (kOuterRowHead + G) &&
+                  sizeof(OuterRow<G>) == 8 * (kOuterRowHead + 2 * G) && sizeof(void*) == 8,
+                  "OuterRow<G> must match the word layout of the outer table");
+    return reinterpret_cast<const OuterRow<G>*>(rows);
+}
+
+template <int WG, int G, int U, bool FLAT, bool SHADOW>
 static void outer_launch(int grid, const OuterTables& T, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
 {
-    const OuterRow<G>* ROWS = reinterpret_cast<const OuterRow<G>*>(T.rows);
+    const OuterRow<G>* ROWS = typed_rows<G>(T.rows);
     const dim3 g(static_cast<unsigned>(grid) * (kBlock / WG)), b(WG);
     const unsigned lds = static_cast<unsigned>(shape.lds_bytes);
-    if (shape.nontemporal) hipLaunchKernelGGL((outer_kernel<WG, G, U, FLAT, PIER, true, SHADOW>), g, b, lds, stream, T.chunks, ROWS, A);
-    else hipLaunchKernelGGL((outer_kernel<WG, G, U, FLAT, PIER, false, SHADOW>), g, b, lds, stream, T.chunks, ROWS, A);
+    if (shape.nontemporal) hipLaunchKernelGGL((outer_kernel<WG, G, U, FLAT, true, SHADOW>), g, b, lds, stream, T.chunks, ROWS, A);
+    else hipLaunchKernelGGL((outer_kernel<WG, G, U, FLAT, false, SHADOW>), g, b, lds, stream, T.chunks, ROWS, A);
 }
 
-template <int WG, int G, int U, bool FLAT, bool PIER>
+template <int WG, int G, int U, bool FLAT>
 static void outer_dispatch_nt(int grid, const OuterTables& T, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
 {
-    if constexpr (PIER) {
-        if (A.shadow) { outer_launch<WG, G, U, FLAT, true, true>(grid, T, A, shape, stream); return; }
-    }
-    outer_launch<WG, G, U, FLAT, PIER, false>(grid, T, A, shape, stream);
+    if (A.shadow) outer_launch<WG, G, U, FLAT, true>(grid, T, A, shape, stream);
+    else outer_launch<WG, G, U, FLAT, false>(grid, T, A, shape, stream);
 }
 
-template <int G, bool FLAT, bool PIER>
+template <int G, bool FLAT>
 static void outer_dispatch_u(int grid, const OuterTables& T, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
 {
     if (shape.wg_threads == 64) {   // one-wave workgroups: one vector per lane per stream only
-        outer_dispatch_nt<64, G, 1, FLAT, PIER>(grid, T, A, shape, stream);
+        outer_dispatch_nt<64, G, 1, FLAT>(grid, T, A, shape, stream);
         return;
     }
     // lanes keep (G + 2) * unroll 16-byte loads in flight; cap the product
     int u = shape.unroll;
     while (u > 1 && (G + 2) * u > 20) u >>= 1;
     switch (u) {
-    case 1: outer_dispatch_nt<kBlock, G, 1, FLAT, PIER>(grid, T, A, shape, stream); break;
-    case 2: outer_dispatch_nt<kBlock, G, 2, FLAT, PIER>(grid, T, A, shape, stream); break;
+    case 1: outer_dispatch_nt<kBlock, G, 1, FLAT>(grid, T, A, shape, stream); break;
+    case 2: outer_dispatch_nt<kBlock, G, 2, FLAT>(grid, T, A, shape, stream); break;
     default:
-        if constexpr ((G + 2) * 4 <= 20) outer_dispatch_nt<kBlock, G, 4, FLAT, PIER>(grid, T, A, shape, stream);
-        else outer_dispatch_nt<kBlock, G, 2, FLAT, PIER>(grid, T, A, shape, stream);
+        if constexpr ((G + 2) * 4 <= 20) outer_dispatch_nt<kBlock, G, 4, FLAT>(grid, T, A, shape, stream);
+        else outer_dispatch_nt<kBlock, G, 2, FLAT>(grid, T, A, shape, stream);
         break;
     }
 }
 
-template <bool FLAT, bool PIER>
+// One kernel template launched as one-wave or four-wave workgroups, streaming or cached.
+#define PIER_LAUNCH_TEAM(KERNEL, FLAT_)                                                                    \
+    do {                                                                                                   \
+        const unsigned lds = static_cast<unsigned>(shape.lds_bytes);                                       \
+        if (shape.wg_threads == 64) {                                                                      \
+            const dim3 g(static_cast<unsigned>(grid) * (kBlock / 64)), b(64);                              \
+            if (shape.nontemporal) hipLaunchKernelGGL((KERNEL<64, FLAT_, true>), g, b, lds, stream, T.chunks, T.rows, A);  \
+            else hipLaunchKernelGGL((KERNEL<64, FLAT_, false>), g, b, lds, stream, T.chunks, T.rows, A);   \
+        } else {                                                                                           \
+            const dim3 g(static_cast<unsigned>(grid)), b(kBlock);                                          \
+            if (shape.nontemporal) hipLaunchKernelGGL((KERNEL<kBlock, FLAT_, true>), g, b, lds, stream, T.chunks, T.rows, A); \
+            else hipLaunchKernelGGL((KERNEL<kBlock, FLAT_, false>), g, b, lds, stream, T.chunks, T.rows, A); \
+        }                                                                                                  \
+    } while (0)
+
+template <bool FLAT>
 static void outer_dispatch_g(int grid, const OuterTables& T, const OuterArgs& A, const LaunchShape& shape, hipStream_t stream)
 {
-    // The register-array kernels win for up to four groups in both phases and for eight groups
-    // in the Pier phase (1-10 % over the loop kernel); the lazy-start phase over eight groups
-    // (ten read streams, two written) measured 0.5-1 % faster in the loop kernel.
-    const bool loop_kernel = !PIER && A.G == 8 && shape.unroll == 1;
-    switch (loop_kernel ? 0 : A.G) {
-    case 1: outer_dispatch_u<1, FLAT, PIER>(grid, T, A, shape, stream); break;
-    case 2: outer_dispatch_u<2, FLAT, PIER>(grid, T, A, shape, stream); break;
-    case 4: outer_dispatch_u<4, FLAT, PIER>(grid, T, A, shape, stream); break;
-    case 8: outer_dispatch_u<8, FLAT, PIER>(grid, T, A, shape, stream); break;
-    default: {
-        const unsigned lds = static_cast<unsigned>(shape.lds_bytes);
-        if (shape.wg_threads == 64) {
-            const dim3 g(static_cast<unsigned>(grid) * (kBlock / 64)), b(64);
-            if (shape.nontemporal) hipLaunchKernelGGL((outer_kernel_anyG<64, FLAT, PIER, true>), g, b, lds, stream, T.chunks, T.rows, A);
-            else hipLaunchKernelGGL((outer_kernel_anyG<64, FLAT, PIER, false>), g, b, lds, stream, T.chunks, T.rows, A);
-        } else {
-            const dim3 g(static_cast<unsigned>(grid)), b(kBlock);
-            if (shape.nontemporal) hipLaunchKernelGGL((outer_kernel_anyG<kBlock, FLAT, PIER, true>), g, b, lds, stream, T.chunks, T.rows, A);
-            else hipLaunchKernelGGL((outer_kernel_anyG<kBlock, FLAT, PIER, false>), g, b, lds, stream, T.chunks, T.rows, A);
-        }
-        break;
-    }
+    // The register-array kernels are 1-10 % faster than the loop kernel at their group counts.
+    switch (A.G) {
+    case 1: outer_dispatch_u<1, FLAT>(grid, T, A, shape, stream); break;
+    case 2: outer_dispatch_u<2, FLAT>(grid, T, A, shape, stream); break;
+    case 4: outer_dispatch_u<4, FLAT>(grid, T, A, shape, stream); break;
+    case 8: outer_dispatch_u<8, FLAT>(grid, T, A, shape, stream); break;
+    default: PIER_LAUNCH_TEAM(outer_kernel_anyG, FLAT); break;
     }
 }
 
@@ -792,7 +834,8 @@ hipError_t launch_outer(const Chunk* chunks, int n_chunks, const uint64_t* rows,
                         bool pier_phase, bool shadow, const LaunchShape& requested, hipStream_t stream)
 {
     if (n_chunks <= 0) return hipSuccess;
-    const LaunchShape shape = resolved(requested, kOuterAutoLds);
+    // the lazy-start pass has AdamW's shape (few streams, light arithmetic): same residency cap
+    const LaunchShape shape = resolved(requested, pier_phase ? kOuterAutoLds : kAdamwAutoLds);
     const OuterTables T{chunks, rows};
     OuterArgs A;
     A.flat_a = flat_a;
@@ -806,12 +849,12 @@ hipError_t launch_outer(const Chunk* chunks, int n_chunks, const uint64_t* rows,
     A.invG = 1.0f / static_cast<float>(G);
     const int grid = grid_for(n_chunks, shape);
     const bool flat = flat_a != nullptr;
-    if (flat) {
-        if (pier_phase) outer_dispatch_g<true, true>(grid, T, A, shape, stream);
-        else outer_dispatch_g<true, false>(grid, T, A, shape, stream);
+    if (pier_phase) {
+        if (flat) outer_dispatch_g<true>(grid, T, A, shape, stream);
+        else outer_dispatch_g<false>(grid, T, A, shape, stream);
     } else {
-        if (pier_phase) outer_dispatch_g<false, true>(grid, T, A, shape, stream);
-        else outer_dispatch_g<false, false>(grid, T, A, shape, stream);
+        if (flat) PIER_LAUNCH_TEAM(lazy_start_kernel, true);
+        else PIER_LAUNCH_TEAM(lazy_start_kernel, false);
     }
     return hipGetLastError();
 }
