@@ -192,23 +192,28 @@ def pier_ctx_set_occupancy(ctx, wg_threads=0, lds_bytes=-1):
     _check(_load().pier_ctx_set_occupancy(ctx.handle, int(wg_threads), int(lds_bytes)))
 
 
+# The keep-alive references are replaced only after the library has accepted the new
+# pointers: after a failed re-bind it still uses the old ones.
 def pier_bind_replica(ctx, replica, p, m, v, grad, grad_is_bf16=False):
-    ctx._keep[("rep", replica)] = (list(p), list(m), list(v), list(grad))
+    keep = (list(p), list(m), list(v), list(grad))
     _check(_load().pier_bind_replica(ctx.handle, int(replica), _ptr_array(p), _ptr_array(m),
                                      _ptr_array(v), _ptr_array(grad), 1 if grad_is_bf16 else 0))
+    ctx._keep[("rep", replica)] = keep
 
 
 def pier_bind_shadow(ctx, replica, w_bf16):
     """w_bf16: list of bfloat16 device tensors (one per model tensor), or None to unbind."""
-    ctx._keep[("shadow", replica)] = list(w_bf16) if w_bf16 is not None else None
+    keep = list(w_bf16) if w_bf16 is not None else None
     _check(_load().pier_bind_shadow(ctx.handle, int(replica), _ptr_array(w_bf16) if w_bf16 is not None else None))
+    ctx._keep[("shadow", replica)] = keep
 
 
 def pier_bind_outer(ctx, loc, anchor, momentum):
     if loc == PIER_LOC_HOST_PINNED and not isinstance(anchor, (list, tuple)):
         anchor, momentum = [anchor], [momentum]
-    ctx._keep["outer"] = (list(anchor), list(momentum))
+    keep = (list(anchor), list(momentum))
     _check(_load().pier_bind_outer(ctx.handle, int(loc), _ptr_array(anchor), _ptr_array(momentum)))
+    ctx._keep["outer"] = keep
 
 
 def pier_inner_adamw(ctx, replica, *, lr, beta1, beta2, eps, weight_decay, step, grad_scale=1.0,
