@@ -50,7 +50,7 @@ typedef enum {
 
 /* Version of this interface: PIER_ABI_VERSION of the header the library was built from.
  * It changes whenever a declared function, struct or enum changes incompatibly. */
-#define PIER_ABI_VERSION 2
+#define PIER_ABI_VERSION 3
 int pier_abi_version(void);
 
 /* Text of the calling thread's most recent error; never NULL; valid until the
@@ -93,6 +93,12 @@ pier_status pier_ctx_set_launch(pier_ctx* ctx, int64_t chunk_elems, int unroll, 
  * -1 = each kernel's measured best (12 waves per compute unit for the AdamW step, 8
  * for the outer step).  Default: 0, -1.  May be called at any time between launches. */
 pier_status pier_ctx_set_occupancy(pier_ctx* ctx, int wg_threads, int lds_bytes);
+
+/* Optional: how many workgroups, hence partial sums, the gradient-norm pass of the clipped
+ * step folds (1 .. 2^20; 0 = the default, 16384; a model with fewer chunks uses one per
+ * chunk).  The fold order, and with it the last bits of the norm, follow this number.
+ * Must be called before the first bind. */
+pier_status pier_ctx_set_norm_fold(pier_ctx* ctx, int n_partials);
 
 /* Binds replica `replica` (0-based).  p, m, v, grad are HOST arrays of n_tensors
  * DEVICE pointers: parameters theta_g, AdamW first and second moments (fp32), and
@@ -149,6 +155,23 @@ pier_status pier_inner_adamw(pier_ctx* ctx, int replica, const pier_adamw_hp* hp
  * The fold uses a fixed order, so the norm is the same in every run. */
 pier_status pier_inner_adamw_clipped(pier_ctx* ctx, int replica, const pier_adamw_hp* hp,
                                      float max_norm, void* hip_stream);
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): pier_inner_adamw_clipped with the norm pass's scratch -
+ * its per-workgroup partial sums and its 24-byte norm/coefficient record - in a static
+ * device array of 131 328 bytes (256 + 8 x 16384) that each GPU holds until the process
+ * ends, instead of in buffers of the context.  The call allocates and frees nothing (the
+ * array's address was resolved when the context first bound a tensor) and clears
+ * nothing: every word of scratch it reads it has written itself.  Same launches, same
+ * arguments, same results bit for bit as pier_inner_adamw_clipped.
+ * PIER_ERR_INVALID_ARG when the context's norm pass folds more than 16384 partial sums
+ * (pier_ctx_set_norm_fold), which the array does not hold; nothing is launched then.
+ * ALL calls on one GPU - any context, any replica, any stream - share that GPU's array:
+ * two such calls that overlap in time race on it, so the caller keeps them on one stream
+ * or orders them with events.  pier_grad_norm_last after this call reads the array, and
+ * is valid only until the next call of this function on the same GPU. */
+pier_status pier_inner_adamw_clipped_static(pier_ctx* ctx, int replica, const pier_adamw_hp* hp,
+                                            float max_norm, void* hip_stream);
+
 /* Norm and coefficient computed by the replica's most recent clipped step: waits for
  * hip_stream, then copies them to the host (either output may be NULL). */
 pier_status pier_grad_norm_last(pier_ctx* ctx, int replica, double* norm_out, float* coef_out,

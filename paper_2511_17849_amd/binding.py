@@ -89,6 +89,8 @@ def _load():
         "pier_bind_outer": (i32, [vp, i32, pp, pp]),
         "pier_inner_adamw": (i32, [vp, i32, ctypes.POINTER(AdamwHP), vp]),
         "pier_inner_adamw_clipped": (i32, [vp, i32, ctypes.POINTER(AdamwHP), f32, vp]),
+        "pier_inner_adamw_clipped_static": (i32, [vp, i32, ctypes.POINTER(AdamwHP), f32, vp]),
+        "pier_ctx_set_norm_fold": (i32, [vp, i32]),
         "pier_grad_norm_last": (i32, [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(f32), vp]),
         "pier_outer_step": (i32, [vp, ctypes.POINTER(OuterHP), vp]),
         "pier_offload_workspace_bytes": (i32, [vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]),
@@ -229,6 +231,17 @@ def pier_inner_adamw_clipped(ctx, replica, *, lr, beta1, beta2, eps, weight_deca
                                             _stream(stream)))
 
 
+def pier_inner_adamw_clipped_static(ctx, replica, *, lr, beta1, beta2, eps, weight_decay, step, max_norm,
+                                    grad_scale=1.0, stream=None):
+    hp = AdamwHP(lr, beta1, beta2, eps, weight_decay, grad_scale, int(step))
+    _check(_load().pier_inner_adamw_clipped_static(ctx.handle, int(replica), ctypes.byref(hp), max_norm,
+                                                   _stream(stream)))
+
+
+def pier_ctx_set_norm_fold(ctx, n_partials=0):
+    _check(_load().pier_ctx_set_norm_fold(ctx.handle, int(n_partials)))
+
+
 def pier_grad_norm_last(ctx, replica, stream=None):
     """(norm, coefficient) of the replica's latest clipped step; synchronises the stream."""
     norm, coef = ctypes.c_double(), ctypes.c_float()
@@ -263,7 +276,7 @@ def pier_offload_stream(ctx, *, outer_lr, mu, phase, chunk_bytes, workspace, com
     return stats
 
 
-ABI_VERSION = 2     # PIER_ABI_VERSION of the header this binding was written against
+ABI_VERSION = 3     # PIER_ABI_VERSION of the header this binding was written against
 
 
 def pier_abi_version():

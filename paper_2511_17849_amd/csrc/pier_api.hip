@@ -11,11 +11,24 @@
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
 
 using namespace pier;
+
+// Scratch of the entry point that allocates nothing (pier_inner_adamw_clipped_static): the
+// norm pass's record (one ClipState, in the first 256 bytes) followed by its per-workgroup
+// partial sums.  One copy per GPU, alive until the process ends, shared by every call on
+// that GPU.  In host code this name is only a handle for hipGetSymbolAddress: the device
+// address is resolved once per device (scratch_for_current_device) and that pointer is what
+// kernels and copies receive.
+constexpr int kStaticNormPartials = 16384;
+constexpr size_t kScratchHead = 256;
+constexpr size_t kScratchBytes = kScratchHead + sizeof(double) * kStaticNormPartials;
+static_assert(sizeof(ClipState) <= kScratchHead, "the norm record must fit the head of the scratch");
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {
 
@@ -32,6 +45,11 @@ pier_status fail(pier_status st, const char* fmt, ...)
     return st;
 }
 
+// Device address of `scratch` on each GPU this process has used the library on.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
 #define PIER_HIP(call)                                                                      \
     do {                                                                                    \
         hipError_t e_ = (call);                                                             \
@@ -39,6 +57,23 @@ pier_status fail(pier_status st, const char* fmt, ...)
             return fail(e_ == hipErrorOutOfMemory ? PIER_ERR_OOM : PIER_ERR_HIP, "%s: %s",  \
                         #call, hipGetErrorString(e_));                                      \
     } while (0)
+
+// Resolves (once per device, with that device current) where this GPU keeps its copy of
+// `scratch`.  Allocates nothing.
+pier_status scratch_for_current_device(int device, void** out)
+{
+    if (device < 0 || device >= kMaxDevices)
+        return fail(PIER_ERR_INVALID_ARG, "device %d: the library tracks devices 0..%d", device, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        PIER_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(PIER_ERR_HIP, "hipGetSymbolAddress returned a null address for the scratch array");
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return PIER_OK;
+}
 
 // Chunking of one offload piece size: the flat index space cut into pieces, each
 // piece owning a contiguous run of chunk-table entries.
@@ -76,9 +111,11 @@ struct pier_ctx {
     std::vector<char> rep_bf16;
     std::vector<char> rep_shadow;
 
-    double* d_partials = nullptr;  // n_replicas * kMaxNormPartials partial sums of the norm pass
+    int norm_partials = kDefaultNormPartials;  // workgroups (= partial sums) of the norm pass, at most
+    double* d_partials = nullptr;  // n_replicas * norm_partials partial sums of the norm pass
     ClipState* d_clip = nullptr;   // one per replica
-    std::vector<char> clip_valid;
+    std::vector<char> clip_valid;  // 0 = no clipped step yet, 1 = record in d_clip, 2 = record in the static scratch
+    void* scratch_ptr = nullptr;   // this GPU's copy of the static scratch (resolved at the first bind)
 
     std::vector<uint64_t> h_rows;  // n_tensors rows of outer_row_words(n_replicas) words
     uint64_t* d_rows = nullptr;
@@ -150,7 +187,7 @@ pier_status allocate_tables(pier_ctx* c)
     PIER_HIP(hipMemcpy(c->d_rows, c->h_rows.data(), sizeof(uint64_t) * c->h_rows.size(),
                        hipMemcpyHostToDevice));
     PIER_HIP(hipMalloc(reinterpret_cast<void**>(&c->d_partials),
-                       sizeof(double) * kMaxNormPartials * c->n_replicas));
+                       sizeof(double) * static_cast<size_t>(c->norm_partials) * c->n_replicas));
     PIER_HIP(hipMalloc(reinterpret_cast<void**>(&c->d_clip), sizeof(ClipState) * c->n_replicas));
     PIER_HIP(hipMemset(c->d_clip, 0, sizeof(ClipState) * c->n_replicas));
     PIER_HIP(hipEventCreate(&c->offload_done));
@@ -169,7 +206,9 @@ pier_status ensure_device(pier_ctx* c)
                         c->device, dev);
         return PIER_OK;
     }
-    const pier_status st = allocate_tables(c);
+    pier_status st = scratch_for_current_device(dev, &c->scratch_ptr);
+    if (st != PIER_OK) return st;
+    st = allocate_tables(c);
     if (st != PIER_OK) {
         release_tables(c);
         return st;
@@ -356,6 +395,17 @@ pier_status pier_ctx_set_launch(pier_ctx* c, int64_t chunk_elems, int unroll, in
     return PIER_OK;
 }
 
+pier_status pier_ctx_set_norm_fold(pier_ctx* c, int n_partials)
+{
+    if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
+    if (c->device >= 0) return fail(PIER_ERR_STATE, "the norm fold width must be set before the first bind");
+    if (n_partials == 0) n_partials = kDefaultNormPartials;
+    if (n_partials < 1 || n_partials > (1 << 20))
+        return fail(PIER_ERR_INVALID_ARG, "n_partials = %d: need 1 .. 2^20, or 0 for the default", n_partials);
+    c->norm_partials = n_partials;
+    return PIER_OK;
+}
+
 pier_status pier_ctx_set_occupancy(pier_ctx* c, int wg_threads, int lds_bytes)
 {
     if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
@@ -487,7 +537,10 @@ pier_status pier_bind_outer(pier_ctx* c, pier_loc loc, float* const* anchor,
     return PIER_OK;
 }
 
-static pier_status inner_adamw_impl(pier_ctx* c, int replica, const pier_adamw_hp* hp, bool clip,
+// Where the norm pass of a clipped step keeps its partial sums and its record.
+enum ClipMode { kNoClip = 0, kClipCtx = 1, kClipStatic = 2 };
+
+static pier_status inner_adamw_impl(pier_ctx* c, int replica, const pier_adamw_hp* hp, ClipMode clip,
                                     float max_norm, void* hip_stream)
 {
     if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
@@ -501,10 +554,19 @@ static pier_status inner_adamw_impl(pier_ctx* c, int replica, const pier_adamw_h
     if (!std::isfinite(hp->lr) || !std::isfinite(hp->eps) || !std::isfinite(hp->weight_decay) ||
         !std::isfinite(hp->grad_scale) || hp->eps < 0.0f)
         return fail(PIER_ERR_INVALID_ARG, "lr / eps / weight_decay / grad_scale not finite, or eps < 0");
-    if (clip && !(max_norm > 0.0f && std::isfinite(max_norm)))
+    if (clip != kNoClip && !(max_norm > 0.0f && std::isfinite(max_norm)))
         return fail(PIER_ERR_INVALID_ARG, "max_norm = %g, need a positive finite value", static_cast<double>(max_norm));
     pier_status st = ensure_device(c);
     if (st != PIER_OK) return st;
+    const int n_partials = std::min(c->n_chunks, c->norm_partials);
+    if (clip == kClipStatic) {
+        const size_t need = kScratchHead + sizeof(double) * static_cast<size_t>(n_partials);
+        if (need > kScratchBytes)
+            return fail(PIER_ERR_INVALID_ARG,
+                        "the norm pass of this context folds %d partial sums and needs %zu bytes of scratch; "
+                        "the static scratch holds %zu (at most %d partial sums)",
+                        n_partials, need, kScratchBytes, kStaticNormPartials);
+    }
 
     AdamwScalars s;
     s.lr = hp->lr;
@@ -521,12 +583,22 @@ static pier_status inner_adamw_impl(pier_ctx* c, int replica, const pier_adamw_h
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const RepPtrs* tab = c->d_rep + static_cast<size_t>(replica) * c->n_tensors;
     const ClipState* cs = nullptr;
-    if (clip) {
-        PIER_HIP(launch_grad_norm(c->d_chunks, c->n_chunks, tab, c->rep_bf16[replica] != 0,
-                                  c->d_partials + static_cast<size_t>(replica) * kMaxNormPartials,
-                                  kMaxNormPartials, max_norm, c->d_clip + replica, stream));
-        c->clip_valid[replica] = 1;
-        cs = c->d_clip + replica;
+    if (clip != kNoClip) {
+        // every partial sum the fold reads and the whole record are rewritten by this call, so
+        // nothing in either buffer has to start at zero
+        double* partials;
+        ClipState* record;
+        if (clip == kClipStatic) {
+            record = static_cast<ClipState*>(c->scratch_ptr);
+            partials = reinterpret_cast<double*>(static_cast<unsigned char*>(c->scratch_ptr) + kScratchHead);
+        } else {
+            record = c->d_clip + replica;
+            partials = c->d_partials + static_cast<size_t>(replica) * c->norm_partials;
+        }
+        PIER_HIP(launch_grad_norm(c->d_chunks, c->n_chunks, tab, c->rep_bf16[replica] != 0, partials,
+                                  n_partials, max_norm, record, stream));
+        c->clip_valid[replica] = static_cast<char>(clip);
+        cs = record;
     }
     PIER_HIP(launch_adamw(c->d_chunks, c->n_chunks, tab, c->rep_bf16[replica] != 0,
                           c->rep_shadow[replica] != 0, s, cs, c->shape, stream));
@@ -535,13 +607,19 @@ static pier_status inner_adamw_impl(pier_ctx* c, int replica, const pier_adamw_h
 
 pier_status pier_inner_adamw(pier_ctx* c, int replica, const pier_adamw_hp* hp, void* hip_stream)
 {
-    return inner_adamw_impl(c, replica, hp, false, 0.0f, hip_stream);
+    return inner_adamw_impl(c, replica, hp, kNoClip, 0.0f, hip_stream);
 }
 
 pier_status pier_inner_adamw_clipped(pier_ctx* c, int replica, const pier_adamw_hp* hp, float max_norm,
                                      void* hip_stream)
 {
-    return inner_adamw_impl(c, replica, hp, true, max_norm, hip_stream);
+    return inner_adamw_impl(c, replica, hp, kClipCtx, max_norm, hip_stream);
+}
+
+pier_status pier_inner_adamw_clipped_static(pier_ctx* c, int replica, const pier_adamw_hp* hp, float max_norm,
+                                            void* hip_stream)
+{
+    return inner_adamw_impl(c, replica, hp, kClipStatic, max_norm, hip_stream);
 }
 
 pier_status pier_grad_norm_last(pier_ctx* c, int replica, double* norm_out, float* coef_out,
@@ -555,8 +633,9 @@ pier_status pier_grad_norm_last(pier_ctx* c, int replica, double* norm_out, floa
     pier_status st = ensure_device(c);
     if (st != PIER_OK) return st;
     ClipState h;
-    PIER_HIP(hipMemcpyAsync(&h, c->d_clip + replica, sizeof h, hipMemcpyDeviceToHost,
-                            static_cast<hipStream_t>(hip_stream)));
+    const ClipState* src = c->clip_valid[replica] == kClipStatic ? static_cast<const ClipState*>(c->scratch_ptr)
+                                                                 : c->d_clip + replica;
+    PIER_HIP(hipMemcpyAsync(&h, src, sizeof h, hipMemcpyDeviceToHost, static_cast<hipStream_t>(hip_stream)));
     PIER_HIP(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
     if (norm_out) *norm_out = h.norm;
     if (coef_out) *coef_out = h.coef;
@@ -950,7 +1029,7 @@ pier_status pier_train_step(pier_ctx* c, const pier_train_cfg* cfg, int64_t t, v
     hp.grad_scale = 1.0f;
     hp.step = t;
     for (int g = 0; g < c->n_replicas; ++g) {
-        st = inner_adamw_impl(c, g, &hp, cfg->clip_norm > 0.0f, cfg->clip_norm, hip_stream);
+        st = inner_adamw_impl(c, g, &hp, cfg->clip_norm > 0.0f ? kClipCtx : kNoClip, cfg->clip_norm, hip_stream);
         if (st != PIER_OK) return st;
     }
     if (!sync) return PIER_OK;

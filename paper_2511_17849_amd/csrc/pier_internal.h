@@ -60,7 +60,7 @@ struct ClipState {
     float reserved;
 };
 
-constexpr int kMaxNormPartials = 16384;  // workgroups (= partial sums) of the norm pass
+constexpr int kDefaultNormPartials = 16384;  // workgroups (= partial sums) of the norm pass unless set otherwise
 
 // clip: nullptr, or the replica's ClipState whose coef multiplies grad_scale.
 // shadow: also write bfloat16(theta) through RepPtrs::w.
@@ -68,7 +68,7 @@ hipError_t launch_adamw(const Chunk* chunks, int n_chunks, const RepPtrs* tab, b
                         bool shadow, const AdamwScalars& s, const ClipState* clip,
                         const LaunchShape& shape, hipStream_t stream);
 
-// Sum of squares of a replica's gradients: n_partials (<= kMaxNormPartials) workgroups
+// Sum of squares of a replica's gradients: n_partials workgroups
 // write one double each, then one workgroup folds them and the clip coefficient into *out.
 hipError_t launch_grad_norm(const Chunk* chunks, int n_chunks, const RepPtrs* tab, bool grad_bf16,
                             double* partials, int n_partials, float max_norm, ClipState* out,
