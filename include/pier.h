@@ -12,10 +12,22 @@
  *  - Every function returns a pier_status and never throws or aborts across the
  *    ABI; pier_last_error() gives the reason of the calling thread's last failure.
  *  - All argument checks happen before anything is enqueued: a call that returns an
- *    error has launched nothing and changed no buffer.
+ *    error has launched nothing and changed no buffer (pier_train_step included: on a
+ *    synchronisation iteration the outer step's arguments are checked before the first
+ *    inner launch).  The only errors that can follow a launch are failures the HIP
+ *    runtime reports while enqueueing (PIER_ERR_HIP).
+ *  - Threads: a context is not synchronised internally.  Calls on DIFFERENT contexts may
+ *    run concurrently from different threads; calls on ONE context - bind calls and
+ *    launches alike - must be serialised by the caller.  pier_last_error() is per thread.
+ *    The host-only helpers (schedules, pier_placement_plan, pier_status_string) are
+ *    re-entrant.
  *  - "device pointer" = memory of the GPU that was current when the context first
  *    touched the GPU (first bind call); the caller keeps that device current for
- *    every later call.  "host pointer" = ordinary host memory unless "pinned" is said.
+ *    every later call.  Bind calls verify that numel elements starting at each pointer
+ *    lie inside the HIP allocation the pointer belongs to (PIER_ERR_INVALID_ARG
+ *    otherwise).  The check is per underlying allocation: for a pointer handed out by a
+ *    sub-allocator (PyTorch's caching allocator) it bounds that allocator's segment, not
+ *    the tensor.  "host pointer" = ordinary host memory unless "pinned" is said.
  *  - Ownership: the caller owns all parameter, state, gradient, staging and pinned
  *    memory and all streams.  The library owns only small tables (pointer lists,
  *    chunk lists, events) that live as long as the context.

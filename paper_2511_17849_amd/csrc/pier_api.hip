@@ -540,8 +540,9 @@ pier_status pier_bind_outer(pier_ctx* c, pier_loc loc, float* const* anchor,
 // Where the norm pass of a clipped step keeps its partial sums and its record.
 enum ClipMode { kNoClip = 0, kClipCtx = 1, kClipStatic = 2 };
 
-static pier_status inner_adamw_impl(pier_ctx* c, int replica, const pier_adamw_hp* hp, ClipMode clip,
-                                    float max_norm, void* hip_stream)
+// Every check of an inner step; launches nothing.
+static pier_status inner_adamw_validate(pier_ctx* c, int replica, const pier_adamw_hp* hp, ClipMode clip,
+                                        float max_norm)
 {
     if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
     if (!hp) return fail(PIER_ERR_INVALID_ARG, "hp is NULL");
@@ -558,8 +559,8 @@ static pier_status inner_adamw_impl(pier_ctx* c, int replica, const pier_adamw_h
         return fail(PIER_ERR_INVALID_ARG, "max_norm = %g, need a positive finite value", static_cast<double>(max_norm));
     pier_status st = ensure_device(c);
     if (st != PIER_OK) return st;
-    const int n_partials = std::min(c->n_chunks, c->norm_partials);
     if (clip == kClipStatic) {
+        const int n_partials = std::min(c->n_chunks, c->norm_partials);
         const size_t need = kScratchHead + sizeof(double) * static_cast<size_t>(n_partials);
         if (need > kScratchBytes)
             return fail(PIER_ERR_INVALID_ARG,
@@ -567,7 +568,13 @@ static pier_status inner_adamw_impl(pier_ctx* c, int replica, const pier_adamw_h
                         "the static scratch holds %zu (at most %d partial sums)",
                         n_partials, need, kScratchBytes, kStaticNormPartials);
     }
+    return PIER_OK;
+}
 
+// The launches of a validated inner step.
+static pier_status inner_adamw_enqueue(pier_ctx* c, int replica, const pier_adamw_hp* hp, ClipMode clip,
+                                       float max_norm, void* hip_stream)
+{
     AdamwScalars s;
     s.lr = hp->lr;
     s.beta1 = hp->beta1;
@@ -586,6 +593,7 @@ static pier_status inner_adamw_impl(pier_ctx* c, int replica, const pier_adamw_h
     if (clip != kNoClip) {
         // every partial sum the fold reads and the whole record are rewritten by this call, so
         // nothing in either buffer has to start at zero
+        const int n_partials = std::min(c->n_chunks, c->norm_partials);
         double* partials;
         ClipState* record;
         if (clip == kClipStatic) {
@@ -603,6 +611,14 @@ static pier_status inner_adamw_impl(pier_ctx* c, int replica, const pier_adamw_h
     PIER_HIP(launch_adamw(c->d_chunks, c->n_chunks, tab, c->rep_bf16[replica] != 0,
                           c->rep_shadow[replica] != 0, s, cs, c->shape, stream));
     return PIER_OK;
+}
+
+static pier_status inner_adamw_impl(pier_ctx* c, int replica, const pier_adamw_hp* hp, ClipMode clip,
+                                    float max_norm, void* hip_stream)
+{
+    const pier_status st = inner_adamw_validate(c, replica, hp, clip, max_norm);
+    if (st != PIER_OK) return st;
+    return inner_adamw_enqueue(c, replica, hp, clip, max_norm, hip_stream);
 }
 
 pier_status pier_inner_adamw(pier_ctx* c, int replica, const pier_adamw_hp* hp, void* hip_stream)
@@ -642,7 +658,8 @@ pier_status pier_grad_norm_last(pier_ctx* c, int replica, double* norm_out, floa
     return PIER_OK;
 }
 
-pier_status pier_outer_step(pier_ctx* c, const pier_outer_hp* hp, void* hip_stream)
+// Every check of the resident outer step; launches nothing.
+static pier_status outer_step_validate(pier_ctx* c, const pier_outer_hp* hp, bool* shadow)
 {
     if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
     pier_status st = check_outer_hp(hp);
@@ -651,8 +668,14 @@ pier_status pier_outer_step(pier_ctx* c, const pier_outer_hp* hp, void* hip_stre
     if (!c->outer_bound || c->outer_loc != PIER_LOC_DEVICE)
         return fail(PIER_ERR_STATE, "anchor and momentum are not bound as device tensors");
     if ((st = ensure_device(c)) != PIER_OK) return st;
+    return outer_shadow_mode(c, shadow);
+}
+
+pier_status pier_outer_step(pier_ctx* c, const pier_outer_hp* hp, void* hip_stream)
+{
     bool shadow = false;
-    if ((st = outer_shadow_mode(c, &shadow)) != PIER_OK) return st;
+    const pier_status st = outer_step_validate(c, hp, &shadow);
+    if (st != PIER_OK) return st;
     PIER_HIP(launch_outer(c->d_chunks, c->n_chunks, c->d_rows, c->n_replicas, nullptr, nullptr, 0,
                           hp->mu, hp->outer_lr, hp->phase == PIER_PHASE_PIER, shadow, c->shape,
                           static_cast<hipStream_t>(hip_stream)));
@@ -679,9 +702,21 @@ pier_status pier_ctx_set_offload_writeback(pier_ctx* c, int trailing)
     return PIER_OK;
 }
 
-pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chunk_bytes,
-                                void* workspace, size_t workspace_bytes, void* compute_stream,
-                                void* h2d_stream, void* d2h_stream, pier_offload_stats* stats)
+// What a validated offload call works with.
+struct OffloadSetup {
+    OffloadPlan* plan = nullptr;
+    size_t piece_bytes = 0;
+    size_t total = 0;
+    int n_pieces = 0;
+    int n_slots = 0;
+    bool shadow = false;
+};
+
+// Every check of the offloaded outer step, and the chunking of this piece size (built and
+// uploaded the first time it is asked for: table memory of the library, no caller buffer).
+// Enqueues nothing on the caller's streams.  N == 0 leaves `out->plan` null.
+static pier_status offload_validate(pier_ctx* c, const pier_outer_hp* hp, size_t chunk_bytes, void* workspace,
+                                    size_t workspace_bytes, OffloadSetup* out)
 {
     if (!c) return fail(PIER_ERR_INVALID_ARG, "ctx is NULL");
     pier_status st = check_outer_hp(hp);
@@ -692,9 +727,7 @@ pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chu
     if (chunk_bytes < 16 || chunk_bytes % 16)
         return fail(PIER_ERR_INVALID_ARG, "chunk_bytes must be a positive multiple of 16");
     if ((st = ensure_device(c)) != PIER_OK) return st;
-    bool shadow = false;
-    if ((st = outer_shadow_mode(c, &shadow)) != PIER_OK) return st;
-    if (stats) std::memset(stats, 0, sizeof *stats);
+    if ((st = outer_shadow_mode(c, &out->shadow)) != PIER_OK) return st;
     if (c->N == 0) return PIER_OK;
 
     const size_t total = static_cast<size_t>(c->N) * 4;
@@ -740,6 +773,25 @@ pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chu
         }
         plan.piece_elems = piece_elems;
     }
+    out->plan = &plan;
+    out->piece_bytes = piece_bytes;
+    out->total = total;
+    out->n_pieces = n_pieces;
+    out->n_slots = n_slots;
+    return PIER_OK;
+}
+
+// The copies and launches of a validated offload call.
+static pier_status offload_enqueue(pier_ctx* c, const pier_outer_hp* hp, const OffloadSetup& S, void* workspace,
+                                   void* compute_stream, void* h2d_stream, void* d2h_stream,
+                                   pier_offload_stats* stats)
+{
+    if (stats) std::memset(stats, 0, sizeof *stats);
+    if (!S.plan) return PIER_OK;      // empty model
+    OffloadPlan& plan = *S.plan;
+    const size_t piece_bytes = S.piece_bytes, total = S.total;
+    const int n_pieces = S.n_pieces, n_slots = S.n_slots;
+    const bool shadow = S.shadow;
 
     hipStream_t sc = static_cast<hipStream_t>(compute_stream);
     hipStream_t sin = static_cast<hipStream_t>(h2d_stream);
@@ -806,6 +858,16 @@ pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chu
         stats->compute_ms = wall;
     }
     return PIER_OK;
+}
+
+pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chunk_bytes,
+                                void* workspace, size_t workspace_bytes, void* compute_stream,
+                                void* h2d_stream, void* d2h_stream, pier_offload_stats* stats)
+{
+    OffloadSetup S;
+    const pier_status st = offload_validate(c, hp, chunk_bytes, workspace, workspace_bytes, &S);
+    if (st != PIER_OK) return st;
+    return offload_enqueue(c, hp, S, workspace, compute_stream, h2d_stream, d2h_stream, stats);
 }
 
 pier_status pier_hbm_probe(void* arena, size_t bytes, size_t granule_bytes, int32_t* class_out,
@@ -1028,24 +1090,39 @@ pier_status pier_train_step(pier_ctx* c, const pier_train_cfg* cfg, int64_t t, v
     hp.weight_decay = cfg->weight_decay;
     hp.grad_scale = 1.0f;
     hp.step = t;
-    for (int g = 0; g < c->n_replicas; ++g) {
-        st = inner_adamw_impl(c, g, &hp, cfg->clip_norm > 0.0f ? kClipCtx : kNoClip, cfg->clip_norm, hip_stream);
+    const ClipMode clip = cfg->clip_norm > 0.0f ? kClipCtx : kNoClip;
+
+    // Everything that can be refused is checked before the first launch: the inner step of every
+    // replica and, on a synchronisation iteration, the whole outer step (bindings, working-copy
+    // rule, offload piece size, workspace, chunking tables).
+    for (int g = 0; g < c->n_replicas; ++g)
+        if ((st = inner_adamw_validate(c, g, &hp, clip, cfg->clip_norm)) != PIER_OK) return st;
+    pier_outer_hp ohp;
+    OffloadSetup S;
+    bool shadow = false;
+    const bool offloaded = sync && c->outer_loc == PIER_LOC_HOST_PINNED;
+    if (sync) {
+        if (cfg->mode == PIER_MODE_DILOCO) {
+            ohp.phase = PIER_PHASE_PIER;   // no lazy start; the DiLoCo paper's recommended scalars
+            ohp.mu = 0.9f;
+            ohp.outer_lr = 0.7f;
+        } else if ((st = pier_outer_schedule(t, cfg->T, &ohp)) != PIER_OK) {
+            return st;
+        }
+        st = offloaded ? offload_validate(c, &ohp, cfg->chunk_bytes, cfg->workspace, cfg->workspace_bytes, &S)
+                       : outer_step_validate(c, &ohp, &shadow);
         if (st != PIER_OK) return st;
     }
-    if (!sync) return PIER_OK;
 
-    pier_outer_hp ohp;
-    if (cfg->mode == PIER_MODE_DILOCO) {
-        ohp.phase = PIER_PHASE_PIER;   // no lazy start; the DiLoCo paper's recommended scalars
-        ohp.mu = 0.9f;
-        ohp.outer_lr = 0.7f;
-    } else if ((st = pier_outer_schedule(t, cfg->T, &ohp)) != PIER_OK) {
-        return st;
-    }
-    if (c->outer_loc == PIER_LOC_HOST_PINNED)
-        return pier_offload_stream(c, &ohp, cfg->chunk_bytes, cfg->workspace, cfg->workspace_bytes,
-                                   hip_stream, cfg->h2d_stream, cfg->d2h_stream, nullptr);
-    return pier_outer_step(c, &ohp, hip_stream);
+    for (int g = 0; g < c->n_replicas; ++g)
+        if ((st = inner_adamw_enqueue(c, g, &hp, clip, cfg->clip_norm, hip_stream)) != PIER_OK) return st;
+    if (!sync) return PIER_OK;
+    if (offloaded)
+        return offload_enqueue(c, &ohp, S, cfg->workspace, hip_stream, cfg->h2d_stream, cfg->d2h_stream, nullptr);
+    PIER_HIP(launch_outer(c->d_chunks, c->n_chunks, c->d_rows, c->n_replicas, nullptr, nullptr, 0, ohp.mu,
+                          ohp.outer_lr, ohp.phase == PIER_PHASE_PIER, shadow, c->shape,
+                          static_cast<hipStream_t>(hip_stream)));
+    return PIER_OK;
 }
 
 pier_status pier_outer_schedule(int64_t t, int64_t T, pier_outer_hp* out)

@@ -103,3 +103,18 @@ extern "C" int pier_inputs_host_free(void* p)
 {
     return p ? static_cast<int>(hipHostFree(p)) : 0;
 }
+
+// Device memory of exactly the size asked for, as its own allocation (torch's caching allocator
+// hands out pieces of larger segments, so the extent of a torch tensor's underlying allocation
+// says nothing about the tensor).
+extern "C" int pier_inputs_device_alloc(void** out, size_t bytes)
+{
+    if (!out) return static_cast<int>(hipErrorInvalidValue);
+    *out = nullptr;
+    return static_cast<int>(hipMalloc(out, bytes ? bytes : 16));
+}
+
+extern "C" int pier_inputs_device_free(void* p)
+{
+    return p ? static_cast<int>(hipFree(p)) : 0;
+}

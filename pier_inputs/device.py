@@ -27,8 +27,29 @@ def _load():
         L.pier_inputs_host_alloc.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_size_t]
         L.pier_inputs_host_free.restype = ctypes.c_int
         L.pier_inputs_host_free.argtypes = [ctypes.c_void_p]
+        L.pier_inputs_device_alloc.restype = ctypes.c_int
+        L.pier_inputs_device_alloc.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_size_t]
+        L.pier_inputs_device_free.restype = ctypes.c_int
+        L.pier_inputs_device_free.argtypes = [ctypes.c_void_p]
         _lib = L
     return _lib
+
+
+class RawDeviceBlock:
+    """One hipMalloc'd block of exactly ``nbytes`` (its own allocation, not a slice of a cached
+    segment); ``ptr`` is the device address.  Freed with the object."""
+
+    def __init__(self, nbytes):
+        p = ctypes.c_void_p()
+        rc = _load().pier_inputs_device_alloc(ctypes.byref(p), nbytes)
+        if rc != 0 or not p.value:
+            raise MemoryError("hipMalloc of %d bytes failed with hipError %d" % (nbytes, rc))
+        self.ptr, self.nbytes = p.value, nbytes
+
+    def __del__(self):
+        if getattr(self, "ptr", None):
+            _load().pier_inputs_device_free(self.ptr)
+            self.ptr = None
 
 
 class _PinnedBlock:

@@ -418,11 +418,9 @@ def test_argument_errors_are_reported_not_launched():
         pier.pier_bind_replica(ctx, 0, host_t, dev_t, dev_t, dev_t)            # host memory
     with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
         pier.pier_bind_replica(ctx, 5, dev_t, dev_t, dev_t, dev_t)             # no such replica
-    short = [torch.zeros(10, device="cuda"), dev_t[1]]
     big = torch.zeros(1000 + 64, device="cuda")
     with pytest.raises(pier.PierError, match="PIER_ERR_ALIGNMENT"):
         pier.pier_bind_replica(ctx, 0, [big.data_ptr() + 2, dev_t[1]], dev_t, dev_t, dev_t)
-    del short
     with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
         pier.pier_bind_replica(ctx, 0, [None, dev_t[1]], dev_t, dev_t, dev_t)  # NULL for a non-empty tensor
     P = [[torch.zeros(k, device="cuda") for k in n] for _ in range(4)]
@@ -459,6 +457,116 @@ def test_argument_errors_are_reported_not_launched():
     for lst in P:
         for t_ in lst:
             assert float(t_.abs().sum()) == 0.0
+
+
+def test_bound_pointer_must_hold_numel_elements_of_its_allocation():
+    """The extent check of the bind calls is made against the underlying allocation of each
+    pointer: a hipMalloc'd block shorter than numel elements, or a pointer so far into a block
+    that numel elements overrun it, is an error code at bind time, not a fault at launch time.
+    (A torch tensor is a slice of a cached segment, so for torch callers the check bounds the
+    segment, not the tensor.)"""
+    import paper_2511_17849_amd as pier
+    from pier_inputs import device as dev
+    MiB = 1 << 20
+    n = [MiB, 24]                                   # 4 MiB of floats: a size no allocator rounds
+    ctx = pier.pier_ctx_create(n, 1)
+    ok = [torch.zeros(k, device="cuda") for k in n]
+    exact = dev.RawDeviceBlock(4 * MiB)             # exactly numel[0] floats
+    short = dev.RawDeviceBlock(2 * MiB)             # half of them
+    pier.pier_bind_replica(ctx, 0, [exact.ptr, ok[1]], ok, ok, ok)                    # fits exactly
+    for bad in ([short.ptr, ok[1]], [exact.ptr + 4, ok[1]]):
+        with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG") as e:
+            pier.pier_bind_replica(ctx, 0, bad, ok, ok, ok)
+        assert "do not fit its allocation" in str(e.value)
+        for kind in range(1, 4):                     # the same for m, v, grad
+            lists = [ok, ok, ok, ok]
+            lists[kind] = bad
+            with pytest.raises(pier.PierError, match="do not fit its allocation"):
+                pier.pier_bind_replica(ctx, 0, *lists)
+        with pytest.raises(pier.PierError, match="do not fit its allocation"):
+            pier.pier_bind_outer(ctx, pier.PIER_LOC_DEVICE, bad, ok)
+        with pytest.raises(pier.PierError, match="do not fit its allocation"):
+            pier.pier_bind_outer(ctx, pier.PIER_LOC_DEVICE, ok, bad)
+    short_w = dev.RawDeviceBlock(MiB)                # half the bytes of numel[0] bfloat16 values
+    with pytest.raises(pier.PierError, match="do not fit its allocation"):
+        pier.pier_bind_shadow(ctx, 0, [short_w.ptr, torch.zeros(24, dtype=torch.bfloat16, device="cuda")])
+    # a bfloat16 gradient needs half the bytes: numel[0] of them fill the 2 MiB block exactly
+    pier.pier_bind_replica(ctx, 0, ok, ok, ok, [short.ptr, ok[1].to(torch.bfloat16)], True)
+    # the offload workspace is checked the same way
+    pa, pm = torch.zeros(sum(n), pin_memory=True), torch.zeros(sum(n), pin_memory=True)
+    pier.pier_bind_outer(ctx, pier.PIER_LOC_HOST_PINNED, pa, pm)
+    ws = dev.RawDeviceBlock(2 * MiB)                 # one staging slot of 2 x 1 MiB
+    with pytest.raises(pier.PierError, match="do not fit its allocation"):
+        pier.pier_offload_stream(ctx, outer_lr=0.7, mu=0.9, phase=PIER, chunk_bytes=MiB,
+                                 workspace=(ws.ptr, 4 * MiB))     # claims twice what the block holds
+    pier.pier_offload_stream(ctx, outer_lr=0.7, mu=0.9, phase=PIER, chunk_bytes=MiB, workspace=(ws.ptr, 2 * MiB))
+    torch.cuda.synchronize()
+    pier.pier_ctx_destroy(ctx)
+
+
+def _snapshot(r):
+    torch.cuda.synchronize()
+    bufs = [x.flat for g in range(r.G) for x in (r.P[g], r.M1[g], r.V[g])] + [r.A.flat, r.Mo.flat]
+    if r.W is not None:
+        bufs += [w.flat.view(torch.int16) for w in r.W]
+    return [b.clone() for b in bufs], bufs
+
+
+@pytest.mark.parametrize("offload", [False, True])
+def test_train_step_that_is_refused_launches_nothing(offload):
+    """On a synchronisation iteration everything the outer step could refuse - the offload piece
+    size, a missing, too small, misaligned or overstated workspace, working copies bound for some
+    replicas only - is checked before the first inner launch: the call returns the error and every
+    buffer is bit-unchanged, so the caller can fix the argument and call again for the same t."""
+    import paper_2511_17849_amd as pier
+    H_ = _harness()
+    numels = [4096, 1000, 36, 0, 70_000]
+    r = H_.Run(numels, 2, seed=53, shadow=True, offload=offload, chunk_bytes=65536 if offload else None)
+    cfg = dict(T=40, r=4, lr_max=3e-4, lr_min=3e-5, warmup_frac=0.1, clip=0.1)
+    r.train_steps(3, **cfg)                                      # t = 1..3: no synchronisation
+    hp = {k: r.hp[k] for k in ("beta1", "beta2", "eps", "weight_decay")}
+    base = dict(T=40, r=4, lr_max=3e-4, lr_min=3e-5, warmup_frac=0.1, clip_norm=0.1, stream=r.stream, **hp)
+    for g in range(r.G):                                         # gradients of iteration 4, as train_steps draws them
+        r.Gd[g].fill_normal(seed=r.seed, stream=0, step=4, std=r.grad_std, hip_stream=r.stream)
+    before, live = _snapshot(r)
+    refused = []
+    if offload:
+        good = dict(workspace=r.workspace, chunk_bytes=r.chunk_bytes, h2d_stream=r.s_in, d2h_stream=r.s_out)
+        small = torch.empty(100, dtype=torch.uint8, device="cuda")
+        refused = [("PIER_ERR_INVALID_ARG", dict(good, workspace=None)),
+                   ("PIER_ERR_INVALID_ARG", dict(good, workspace=small)),
+                   ("PIER_ERR_INVALID_ARG", dict(good, chunk_bytes=1000)),
+                   ("PIER_ERR_INVALID_ARG", dict(good, chunk_bytes=0))]
+    else:
+        good = {}
+    for status, kw in refused:
+        with pytest.raises(pier.PierError, match=status):
+            pier.pier_train_step(r.ctx, 4, **base, **kw)
+    if offload:
+        # misaligned workspace: a pointer 4 bytes into a large enough block (raw pointer through the ABI)
+        wb = r.workspace.numel()
+        blk = torch.empty(wb + 64, dtype=torch.uint8, device="cuda")
+        import ctypes
+        L = pier.binding._load()
+        cfgs = pier.TrainCfg(40, 4, pier.PIER_MODE_PIER, 3e-4, 3e-5, 0.1, hp["beta1"], hp["beta2"], hp["eps"],
+                             hp["weight_decay"], 0.1, r.chunk_bytes, blk.data_ptr() + 4, wb,
+                             r.s_in.cuda_stream or None, r.s_out.cuda_stream or None)
+        assert L.pier_train_step(r.ctx.handle, ctypes.byref(cfgs), 4, r.stream.cuda_stream or None) == 2   # PIER_ERR_ALIGNMENT
+    # working copies bound for one replica only: the outer step refuses, before anything ran
+    kept = r.W[1].tensors
+    pier.pier_bind_shadow(r.ctx, 1, None)
+    with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):
+        pier.pier_train_step(r.ctx, 4, **base, **good)
+    pier.pier_bind_shadow(r.ctx, 1, kept)
+    torch.cuda.synchronize()
+    for was, now in zip(before, live):
+        assert torch.equal(was, now)
+    # the same iteration with good arguments still works and matches the oracle
+    r.t = 3
+    r.train_steps(1, **cfg)
+    rep = r.check("train_step after refused calls")
+    assert rep["bit_exact"], rep
+    assert [(t, ph) for t, ph, _, _ in r.sync_log] == [(4, WARMUP)]
 
 
 def test_plain_c_client_of_the_abi(tmp_path):
