@@ -5,6 +5,9 @@ oracle follows the same update sequence on a sample of element indices (all of t
 for small cases).  Gradients are synthesised on the device by pier_inputs and the
 oracle reads its sample of each gradient back, so both sides consume identical bits.
 """
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import torch
 
@@ -29,10 +32,11 @@ def rel_ok(got, ref, rel=1e-5, floor=1e-12):
     return np.abs(got - ref64) <= rel * np.abs(ref64) + floor
 
 
-def sample_indices(numels, n_strided=1 << 16, chunk=16384, piece=None, pad=0):
+def sample_indices(numels, n_strided=1 << 16, chunk=16384, piece=None, pad=0, windows=()):
     """Deterministic sample of flat element indices: a strided sweep, the first and
-    last 8 elements of every tensor, and +-8 around every chunk (and piece) boundary
-    near the start of each tensor.  Indices address the padded flat buffer."""
+    last 8 elements of every tensor, +-8 around every chunk (and piece) boundary
+    near the start of each tensor, and every element of the contiguous ``windows``
+    [(first flat index, length), ...].  Indices address the padded flat buffer."""
     starts, off = [], 0
     for n in numels:
         starts.append(off)
@@ -59,7 +63,67 @@ def sample_indices(numels, n_strided=1 << 16, chunk=16384, piece=None, pad=0):
             k = max(1, n_strided * n // max(N, 1))
             if n:
                 idx.append(s + np.unique(np.linspace(0, n - 1, k).astype(np.int64)))
+    for lo, n in windows:
+        assert pad == 0 and 0 <= lo and lo + n <= N
+        idx.append(np.arange(lo, lo + n, dtype=np.int64))
     out = np.unique(np.concatenate([np.asarray(i, dtype=np.int64) for i in idx]))
+    return out
+
+
+def dense_windows(numels, piece=None, length=1 << 22):
+    """Contiguous windows of ``length`` elements for the full-size cases: one inside the largest
+    tensor (4096 chunks of 1024 elements), one centred on the boundary behind the largest tensor,
+    one centred on the start of the middle tensor of the list (where small tensors follow each
+    other) and, for the offload path, one centred on a piece boundary in the middle of the model."""
+    starts = np.concatenate([[0], np.cumsum(numels)])
+    N = int(starts[-1])
+    big = int(np.argmax(numels))
+    half = length // 2
+    wins = [(int(starts[big]) + (numels[big] - length) // 2 // 1024 * 1024 + 512, length)]   # off the chunk grid
+    for centre in (int(starts[big + 1]), int(starts[len(numels) // 2])):
+        wins.append((min(max(0, centre - half), N - length), length))
+    if piece:
+        b = (N // piece // 2) * piece
+        wins.append((min(max(0, b - half), N - length), length))
+    return [w for w in wins if numels[big] >= length and N >= 4 * length]
+
+
+# The oracle is single-threaded code; the harness may run it on disjoint slices of the
+# sample from several threads at once (the update is elementwise, ctypes drops the GIL).
+_WORKERS = max(1, min(16, os.cpu_count() or 1))
+_pool = None
+
+
+def _sliced(fn, n, slicer):
+    """fn(*slicer(lo, hi)) over [0, n) cut into one slice per worker."""
+    global _pool
+    if n < (1 << 21) or _WORKERS == 1:
+        fn(*slicer(0, n))
+        return
+    if _pool is None:
+        O.default()
+        _pool = ThreadPoolExecutor(max_workers=_WORKERS)
+    cuts = np.linspace(0, n, _WORKERS + 1).astype(np.int64)
+    futs = [_pool.submit(fn, *slicer(int(a), int(b))) for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+    for f in futs:
+        f.result()
+
+
+def oracle_adamw(p, m, v, g, **kw):
+    _sliced(lambda *a: O.adamw(*a, **kw), p.size, lambda lo, hi: (p[lo:hi], m[lo:hi], v[lo:hi], g[lo:hi]))
+
+
+def oracle_outer(thetas, a, M, **kw):
+    _sliced(lambda th, a_, M_: O.outer(th, a_, M_, **kw), a.size,
+            lambda lo, hi: ([t[lo:hi] for t in thetas], a[lo:hi], M[lo:hi]))
+
+
+def oracle_to_bf16(x):
+    out = np.empty(x.size, np.uint16)
+
+    def part(src, dst):
+        dst[:] = O.to_bf16(src)
+    _sliced(part, x.size, lambda lo, hi: (x[lo:hi], out[lo:hi]))
     return out
 
 
@@ -79,13 +143,17 @@ class Run:
 
     def __init__(self, numels, G, *, grad_bf16=False, hp=None, seed=0, param_std=0.02, grad_std=1e-3,
                  pad=0, launch=None, offload=False, chunk_bytes=None, sample=None, shared_grad=False,
-                 stream=None, arena=None, shadow=False):
+                 stream=None, arena=None, shadow=False, full_checks=False):
         self.numels, self.G, self.pad = list(numels), G, pad
         self.grad_bf16 = grad_bf16
         self.hp = hp or dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
         self.seed, self.grad_std = seed, grad_std
         self.offload, self.chunk_bytes = offload, chunk_bytes
         self.want_stats = True      # False: the offload call returns after enqueueing
+        # whole-buffer checks on the device (every element, not the sample): see full_* below
+        self.full_checks = full_checks and pad == 0
+        self.full_log = []
+        self._outer_calls = 0
         self.stream = stream or torch.cuda.current_stream()
         self.t = 0
         gdt = torch.bfloat16 if grad_bf16 else torch.float32
@@ -143,12 +211,13 @@ class Run:
             pier.pier_bind_outer(self.ctx, pier.PIER_LOC_DEVICE, self.A.tensors, self.Mo.tensors)
 
         # oracle shadow on the sample
+        self.dense = sample is None and pad == 0      # the sample is the whole flat buffer, in order
         if sample is None:       # every element of every tensor (padding between tensors excluded)
             st = self.P[0].starts
             sample = np.concatenate([np.arange(s, s + n, dtype=np.int64) for s, n in zip(st, self.numels)]
                                     + [np.zeros(0, np.int64)])
         self.idx = np.asarray(sample, dtype=np.int64)
-        self.idx_d = torch.from_numpy(self.idx).cuda()
+        self.idx_d = None if self.dense else torch.from_numpy(self.idx).cuda()
         self.oP = [self._take(self.P[g].flat) for g in range(G)]
         self.oM1 = [np.zeros(self.idx.size, np.float32) for _ in range(G)]
         self.oV = [np.zeros(self.idx.size, np.float32) for _ in range(G)]
@@ -157,13 +226,27 @@ class Run:
         self.oW = [np.zeros(self.idx.size, np.uint16) for _ in range(G)] if shadow else None
 
     def _take(self, flat):
-        if flat.is_cuda:
-            x = flat[self.idx_d]
-        else:
-            x = flat[torch.from_numpy(self.idx)]
-        if x.dtype == torch.bfloat16:
-            return np.ascontiguousarray(x.view(torch.int16).cpu().numpy().view(np.uint16))
-        return np.ascontiguousarray(x.cpu().numpy())
+        """The sampled elements of a flat buffer as a numpy array (bfloat16 as uint16 bit patterns),
+        through the pinned staging buffer."""
+        n = self.idx.size
+        bf16 = flat.dtype == torch.bfloat16
+        out = np.empty(n, np.uint16 if bf16 else np.float32)
+        stage = _staging(flat.dtype)
+        idx_h = None if (self.dense or flat.is_cuda) else torch.from_numpy(self.idx)
+        for lo in range(0, n, _STAGE_ELEMS):
+            hi = min(n, lo + _STAGE_ELEMS)
+            if self.dense:
+                src = flat[lo:hi]
+            elif flat.is_cuda:
+                src = flat[self.idx_d[lo:hi]]
+            else:
+                src = flat[idx_h[lo:hi]]
+            st = stage[:hi - lo]
+            st.copy_(src)
+            if flat.is_cuda:
+                torch.cuda.synchronize()
+            out[lo:hi] = st.view(torch.int16).numpy().view(np.uint16) if bf16 else st.numpy()
+        return out
 
     def _oracle_sumsq(self, g):
         """Sum of squares of the whole gradient of replica g's buffers, by the oracle, tensor by
@@ -196,7 +279,9 @@ class Run:
                 gs = self._take(self.Gd[g].flat)           # synchronises; the oracle's copy of the bits
                 if clip is None:
                     pier.pier_inner_adamw(self.ctx, g, step=self.t, stream=self.stream, **self.hp)
-                    O.adamw(self.oP[g], self.oM1[g], self.oV[g], gs, step=self.t, **self.hp)
+                    oracle_adamw(self.oP[g], self.oM1[g], self.oV[g], gs, step=self.t, **self.hp)
+                    if self.full_checks and self.t == 1 and self.hp.get("grad_scale", 1.0) == 1.0:
+                        self.full_check_first_adamw_step(g)
                 else:
                     pier.pier_inner_adamw_clipped(self.ctx, g, step=self.t, max_norm=clip, stream=self.stream,
                                                   **self.hp)
@@ -204,11 +289,11 @@ class Run:
                     coef = O.clip_coef(ss, clip)
                     hp = dict(self.hp)
                     hp["grad_scale"] = hp.get("grad_scale", 1.0) * coef
-                    O.adamw(self.oP[g], self.oM1[g], self.oV[g], gs, step=self.t, **hp)
+                    oracle_adamw(self.oP[g], self.oM1[g], self.oV[g], gs, step=self.t, **hp)
                     norm_d, coef_d = pier.pier_grad_norm_last(self.ctx, g, stream=self.stream)
                     self.clip_log.append((np.sqrt(ss), coef, norm_d, coef_d))
                 if self.oW is not None:
-                    self.oW[g] = O.to_bf16(self.oP[g])
+                    self.oW[g] = oracle_to_bf16(self.oP[g])
 
     def train_steps(self, n, *, T, r, diloco=False, lr_max, lr_min, warmup_frac=0.02, clip=0.0):
         """n iterations through pier_train_step (inner steps with the scheduled learning rate,
@@ -233,17 +318,18 @@ class Run:
                                  stream=self.stream, **hp, **kw)
             for g in range(self.G):
                 coef = O.clip_coef(self._oracle_sumsq(g), clip) if clip > 0 else 1.0
-                O.adamw(self.oP[g], self.oM1[g], self.oV[g], gs[g], step=t, lr=lr, grad_scale=coef, **hp)
+                oracle_adamw(self.oP[g], self.oM1[g], self.oV[g], gs[g], step=t, lr=lr, grad_scale=coef, **hp)
                 if self.oW is not None:
-                    self.oW[g] = O.to_bf16(self.oP[g])
+                    self.oW[g] = oracle_to_bf16(self.oP[g])
             if t % r == 0:
                 ph, mu, lr_o = (O.PIER, 0.9, 0.7) if diloco else O.outer_scalars(t, T)
-                O.outer(self.oP, self.oA, self.oMo, mu=mu, lr=lr_o, phase=ph)
+                oracle_outer(self.oP, self.oA, self.oMo, mu=mu, lr=lr_o, phase=ph)
                 if self.oW is not None and ph == O.PIER:
-                    self.oW = [O.to_bf16(p) for p in self.oP]
+                    self.oW = [oracle_to_bf16(p) for p in self.oP]
                 self.sync_log.append((t, ph, round(mu, 4), lr_o))
 
     def outer(self, *, mu, lr, phase):
+        before = self.full_outer_before(phase) if self.full_checks else None
         if self.offload:
             self.stats = pier.pier_offload_stream(self.ctx, outer_lr=lr, mu=mu, phase=phase,
                                                   chunk_bytes=self.chunk_bytes, workspace=self.workspace,
@@ -251,9 +337,80 @@ class Run:
                                                   d2h_stream=self.s_out, want_stats=self.want_stats)
         else:
             pier.pier_outer_step(self.ctx, outer_lr=lr, mu=mu, phase=phase, stream=self.stream)
-        O.outer(self.oP, self.oA, self.oMo, mu=mu, lr=lr, phase=phase)
+        oracle_outer(self.oP, self.oA, self.oMo, mu=mu, lr=lr, phase=phase)
         if self.oW is not None and phase == O.PIER:
-            self.oW = [O.to_bf16(p) for p in self.oP]
+            self.oW = [oracle_to_bf16(p) for p in self.oP]
+        if before is not None:
+            self.full_outer_after(before, mu, lr, phase)
+        self._outer_calls += 1
+
+    # ---------------------------------------------------------------- whole-buffer checks
+    #
+    # Properties that hold for EVERY element, evaluated on the device with the array library's
+    # own elementwise fp32 operations (one IEEE operation per call, no fusion), in slices so that
+    # temporaries stay small.  They say that every element was updated exactly once: an element a
+    # launch skipped keeps m = v = 0 resp. its old anchor, one it visited twice breaks the
+    # single-step closed forms.
+    _SLICE = 1 << 27
+
+    def _slices(self):
+        N = sum(self.numels)
+        return [(lo, min(N, lo + self._SLICE)) for lo in range(0, N, self._SLICE)]
+
+    @staticmethod
+    def _dev(t, lo, hi):
+        x = t[lo:hi]
+        return x if x.is_cuda else x.cuda()
+
+    def full_check_first_adamw_step(self, g):
+        """After replica g's first step from m = v = 0 with grad_scale 1: m = (1 - beta1) g and
+        v = ((1 - beta2) g) g exactly, and theta differs from the initial model (still in the
+        anchor) everywhere: the step is lr (+-1 + wd theta), far above an ulp of theta."""
+        om1 = float(np.float32(1.0) - np.float32(self.hp["beta1"]))
+        om2 = float(np.float32(1.0) - np.float32(self.hp["beta2"]))
+        torch.cuda.synchronize()
+        moved = 0
+        for lo, hi in self._slices():
+            gr = self.Gd[g].flat[lo:hi].float()
+            assert torch.equal(self.M1[g].flat[lo:hi], gr * om1), ("m after step 1", g, lo)
+            assert torch.equal(self.V[g].flat[lo:hi], (gr * om2) * gr), ("v after step 1", g, lo)
+            moved += int((self.P[g].flat[lo:hi] != self._dev(self.A.flat, lo, hi)).sum())
+        assert moved == sum(self.numels), ("theta untouched somewhere", g, moved)
+        self.full_log.append(("adamw step 1", g, moved))
+
+    def full_outer_before(self, phase):
+        """Device copies of what the checks after the step need of the state before it: the old
+        anchor (lazy start, and the first Pier step) and the old momentum (lazy start)."""
+        torch.cuda.synchronize()
+        keep = lambda t: t.cuda() if not t.is_cuda else t.clone()
+        need_a = phase == O.WARMUP or self._outer_calls == 0
+        return {"a": keep(self.A.flat) if need_a else None,
+                "M": keep(self.Mo.flat) if phase == O.WARMUP else None}
+
+    def full_outer_after(self, before, mu, lr, phase):
+        """Lazy start: anchor == model (replica 0) and M == mu M_old + (model - anchor_old).
+        Pier: every replica == new anchor; and, when M_old was zero (the first synchronisation),
+        new anchor == old anchor + lr (mu M + M) with M the new momentum (= delta)."""
+        torch.cuda.synchronize()
+        mu32, lr32 = float(np.float32(mu)), float(np.float32(lr))
+        m_was_zero = self._outer_calls == 0
+        nonzero = 0
+        for lo, hi in self._slices():
+            a_new, M_new = self._dev(self.A.flat, lo, hi), self._dev(self.Mo.flat, lo, hi)
+            a_old = before["a"][lo:hi] if before["a"] is not None else None
+            M_old = before["M"][lo:hi] if before["M"] is not None else None
+            if phase == O.WARMUP:
+                th = self.P[0].flat[lo:hi]
+                assert torch.equal(a_new, th), ("lazy start: anchor is not the model", lo)
+                assert torch.equal(M_new, M_old * mu32 + (th - a_old)), ("lazy start: momentum", lo)
+            else:
+                for g in range(self.G):
+                    assert torch.equal(self.P[g].flat[lo:hi], a_new), ("replica not re-synchronised", g, lo)
+                if m_was_zero:
+                    assert torch.equal(a_new, a_old + (M_new * mu32 + M_new) * lr32), ("anchor vs momentum", lo)
+            nonzero += int((M_new != 0).sum())
+        self.full_log.append(("outer", phase, nonzero))
+        assert nonzero > 0.99 * sum(self.numels)
 
     def device_state(self):
         torch.cuda.synchronize()

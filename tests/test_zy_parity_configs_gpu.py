@@ -1,11 +1,20 @@
-"""(Collected after the small-case file on purpose: these cases hold up to ~215 GB of HBM and
+"""(Collected after the small-case file on purpose: these cases hold up to ~245 GB of HBM and
 53 GB of pinned host memory, so they run when nothing else is left to run.)
 
 GPU parity at the full sizes of the benchmark configurations, in the launch
-configuration bench.py times (library defaults), on a deterministic sample of element
-indices: a strided sweep of 2^16 positions plus the first/last elements of every tensor
-and the neighbourhood of chunk and offload-piece boundaries.  The update is
-elementwise, so the oracle run on the sampled elements alone is exact for them."""
+configuration bench.py times (library defaults).  Three layers of evidence:
+  * the oracle, element by element, on a deterministic sample: a strided sweep of 2^16
+    positions, the first/last elements of every tensor, the neighbourhood of chunk and
+    offload-piece boundaries, and contiguous windows of 2^22 elements (4096 chunks each)
+    inside the largest tensor, across the boundary behind it, across the run of small tensors
+    in the middle of the model and across an offload-piece boundary (the update is
+    elementwise, so the oracle run on the sampled elements alone is exact for them);
+  * GPT-2 small on EVERY element for a lazy-start round of the full 50 inner steps and a
+    Pier round;
+  * whole-buffer properties checked on the device for every element at every size
+    (pier_harness.Run.full_*): the closed form of the first AdamW step, theta moved
+    everywhere, anchor == model after a lazy-start synchronisation, every replica == anchor
+    after a Pier step, the anchor/momentum relation of the first Pier step."""
 import gc
 
 import numpy as np
@@ -54,16 +63,18 @@ def _arena():
     return a
 
 
-def _run_config(name, chunk_bytes=None, expect_phases=None, arena=None):
+def _run_config(name, chunk_bytes=None, expect_phases=None, arena=None, windows=True, full_checks=True):
     import pier_harness as H_
     from pier_inputs import shapes
     w = shapes.workloads()[name]
     piece = (chunk_bytes // 4) if w.offload else None
-    idx = H_.sample_indices(w.numels, chunk=1024, piece=piece)
-    _log("%s: N=%d G=%d H=%d rounds=%d sampled=%d" % (name, w.N, w.G, w.H, w.rounds, idx.size))
+    wins = H_.dense_windows(w.numels, piece=piece) if windows else []
+    idx = H_.sample_indices(w.numels, chunk=1024, piece=piece, windows=wins)
+    _log("%s: N=%d G=%d H=%d rounds=%d sampled=%d windows=%s" % (name, w.N, w.G, w.H, w.rounds, idx.size, wins))
     hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay)
     r = H_.Run(w.numels, w.G, grad_bf16=w.grad_bf16, hp=hp, seed=w.seed, param_std=w.param_std,
-               grad_std=w.grad_std, offload=w.offload, chunk_bytes=chunk_bytes, sample=idx, arena=arena)
+               grad_std=w.grad_std, offload=w.offload, chunk_bytes=chunk_bytes, sample=idx, arena=arena,
+               full_checks=full_checks)
     phases = []
     try:
         for k in range(w.rounds):
@@ -82,6 +93,10 @@ def _run_config(name, chunk_bytes=None, expect_phases=None, arena=None):
             assert phases == expect_phases, phases
         st = r.device_state()
         assert np.abs(st["Mo"]).max() > 1e-6
+        _log("%s whole-buffer checks: %s" % (name, r.full_log))
+        if full_checks:
+            assert len([x for x in r.full_log if x[0] == "adamw step 1"]) == w.G
+            assert len([x for x in r.full_log if x[0] == "outer"]) == w.rounds
         return r, rep
     except Exception:
         del r
@@ -94,6 +109,40 @@ def test_config2_gpt2_small_four_rounds_across_the_schedule():
     r, rep = _run_config("gpt2_small", expect_phases=[(WARMUP, 0.9), (WARMUP, 0.9), (PIER, 0.99), (PIER, 0.95)])
     del r
     _free()
+
+
+@pytest.mark.timeout(600)
+def test_config2_gpt2_small_every_element():
+    """GPT-2 small shapes, G = 4, the oracle on EVERY one of the 124 439 808 elements of every
+    buffer: a lazy-start round of the full H = 50 inner steps and its synchronisation, then a
+    Pier round (5 inner steps, mu 0.99) - 1.1e11 oracle element updates, spread over the host
+    cores.  A second run of the same case in a different launch shape (four-wave workgroups,
+    4096-element chunks, no residency cap) must give the same whole buffers bit for bit."""
+    import pier_harness as H_
+    from pier_inputs import shapes
+    w = shapes.workloads()["gpt2_small"]
+    hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay)
+    _log("config 2, every element: N=%d G=%d" % (w.N, w.G))
+    r = H_.Run(w.numels, w.G, hp=hp, seed=w.seed, full_checks=True)
+    other = H_.Run(w.numels, w.G, hp=hp, seed=w.seed, sample=np.arange(8, dtype=np.int64),
+                   launch=dict(chunk_elems=4096, unroll=2, wg_threads=256, lds_bytes=0))
+    try:
+        for k, (H, ph, mu, lr) in enumerate([(w.H, WARMUP, 0.9, 0.0), (5, PIER, 0.99, 40.0 / 110.0)]):
+            for run in (r, other):
+                run.inner_steps(H, shared_stream=(ph == WARMUP))
+                run.outer(mu=mu, lr=lr, phase=ph)
+            rep = r.check("config 2 dense, round %d" % k)
+            _log("config 2 dense round %d: %s" % (k, rep))
+            assert rep["bit_exact"] and rep["n_sampled"] == w.N, rep
+        torch.cuda.synchronize()
+        for g in range(w.G):
+            for a, b in ((r.P[g], other.P[g]), (r.M1[g], other.M1[g]), (r.V[g], other.V[g])):
+                assert torch.equal(a.flat, b.flat)
+        assert torch.equal(r.A.flat, other.A.flat) and torch.equal(r.Mo.flat, other.Mo.flat)
+        _log("config 2 dense whole-buffer checks: %s" % r.full_log)
+    finally:
+        del r, other
+        _free()
 
 
 @pytest.mark.timeout(300)
@@ -269,7 +318,9 @@ def test_placement_probe_is_repeatable_and_rejects_bad_arguments():
 @pytest.mark.timeout(600)
 def test_config4_gpt2_xl_in_probed_arena():
     arena = _arena()
-    r, rep = _run_config("gpt2_xl", arena=arena)
+    # (the arena leaves 8 GiB of HBM free: the sparse sample only; windows and whole-buffer checks
+    # run in the plain-allocation case above)
+    r, rep = _run_config("gpt2_xl", arena=arena, windows=False, full_checks=False)
     # placement policy: theta_g and m_g share an address class, v_g and grad_g share another
     # (first-fit may have to deviate for a replica or two when a class runs out of room), and
     # the outer step's ten buffers lie in two classes, five in each
