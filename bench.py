@@ -28,6 +28,8 @@ HBM_PEAK_GBPS = 8000.0        # MI355X published HBM3E peak
 # same counters' reading of a plain copy kernel); summary in
 # profiles/kernels_gpt2_xl_hbm_traffic_pmc.md.  Only valid for the workload it was taken on.
 MEASURED_TRAFFIC_GB = {"gpt2_xl": {"adamw": 44.003, "outer": 125.005}}
+TRAFFIC_NOTE = ("GB per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script "
+                "(profiles/kernels_gpt2_xl_hbm_traffic_pmc.md); a constant, not measured by this run")
 
 
 def parse():
@@ -40,6 +42,8 @@ def parse():
     ap.add_argument("--no-offload", action="store_true", help="skip the host-offload measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-arena", action="store_true", help="plain allocations instead of the probed arena")
+    ap.add_argument("--no-plain", action="store_true",
+                    help="skip the closing measurement of the same kernels on plain allocations")
     ap.add_argument("--chunk-mib", type=int, default=0,
                     help="offload piece size; 0 = 256 MiB, or a sixteenth of one array (in steps of "
                          "16 MiB) when that is smaller, so that small models still fill the pipeline")
@@ -48,7 +52,7 @@ def parse():
     ap.add_argument("--no-trailing", action="store_true",
                     help="host-offload workloads: make the compute stream wait for the copy-back")
     ap.add_argument("--variants", action="store_true",
-                    help="also time the clipped step, the bf16-working-copy kernels and the lazy-start outer step")
+                    help="also time the clipped step and the bf16-working-copy kernels")
     return ap.parse_args()
 
 
@@ -106,25 +110,67 @@ def cpu_baseline(w):
     return out
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not "
-              "supported, run with --gpus 1" % args.gpus, file=sys.stderr)
-        sys.exit(2)
-    from pier_inputs import shapes
-    baseline = None
-    if not args.no_cpu_baseline:
-        baseline = cpu_baseline(shapes.workloads()[args.workload])      # before any GPU call
+class State:
+    """All buffers of the workload on the GPU (placed through the library's plan when an arena is
+    given), initialised, and a context bound to them."""
+
+    def __init__(self, w, arena, host_outer, stream):
+        import torch
+        import paper_2511_17849_amd as pier
+        from pier_inputs import device as dev
+        self.w, self.stream, self.host_outer = w, stream, host_outer
+        G, numels = w.G, w.numels
+        gdt = torch.bfloat16 if w.grad_bf16 else torch.float32
+        # the 7B configuration keeps one gradient buffer for all replicas (each launch reads it whole,
+        # so the traffic is the same): nine of its 26 GiB buffers fit the three address classes, and
+        # only with a single gradient buffer do every replica's four streams lie in two classes
+        B = pier.ModelBuffers(w.N, G, grad_dtype=gdt, arena=arena, outer_on_device=not host_outer,
+                              shared_grad=host_outer)
+        wrap = lambda ts, cs: [dev.FlatList.wrap(t, numels, c) for t, c in zip(ts, cs)]
+        self.P, self.M1 = wrap(B.theta, B.classes["theta"]), wrap(B.m, B.classes["m"])
+        self.V, self.Gd = wrap(B.v, B.classes["v"]), wrap(B.grad, B.classes["grad"])
+        if host_outer:
+            self.A = dev.FlatList(numels, pinned=True, zero=False)
+            self.Mo = dev.FlatList(numels, pinned=True, zero=False)
+        else:
+            self.A = dev.FlatList.wrap(B.anchor, numels, B.classes["anchor"])
+            self.Mo = dev.FlatList.wrap(B.momentum, numels, B.classes["momentum"])
+        with torch.cuda.stream(stream):
+            for fl in self.M1 + self.V:
+                fl.flat.zero_()
+            dev.init_params(self.P[0], w)
+            for g in range(1, G):
+                self.P[g].flat.copy_(self.P[0].flat)
+            for g in range(1 if host_outer else G):
+                self.Gd[g].fill_normal(seed=w.seed, stream=g, step=1, std=w.grad_std, hip_stream=stream)
+        stream.synchronize()
+        self.A.flat.copy_(self.P[0].flat)
+        self.Mo.flat.zero_()
+        torch.cuda.synchronize()
+        self.ctx = pier.pier_ctx_create(numels, G)
+        for g in range(G):
+            pier.pier_bind_replica(self.ctx, g, self.P[g].tensors, self.M1[g].tensors, self.V[g].tensors,
+                                   self.Gd[g].tensors, w.grad_bf16)
+        if host_outer:
+            pier.pier_bind_outer(self.ctx, pier.PIER_LOC_HOST_PINNED, self.A.flat, self.Mo.flat)
+        else:
+            pier.pier_bind_outer(self.ctx, pier.PIER_LOC_DEVICE, self.A.tensors, self.Mo.tensors)
+        self.t = 0
+
+    def inner_round(self, H, hp):
+        import paper_2511_17849_amd as pier
+        for _ in range(H):
+            self.t += 1
+            for g in range(self.w.G):
+                pier.pier_inner_adamw(self.ctx, g, step=self.t, stream=self.stream, **hp)
+
+
+def run_placed(args, w):
+    """The timed rounds (and the variants and the offload stream) on placed buffers; returns the
+    result record and whether an arena was used.  Everything it allocated is released on return."""
     import torch
     import paper_2511_17849_amd as pier
     from pier_inputs import device as dev
-
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
-    torch.cuda.set_device(0)
-    w = shapes.workloads()[args.workload]
     N, G = w.N, w.G
     H = args.inner_steps or w.H
     K, W = args.steps, args.warmup
@@ -144,47 +190,25 @@ def main():
     # HBM layout: one arena over (almost) all free HBM is probed for its address classes and
     # the buffers one launch streams together are carved from different classes; if the
     # arena cannot be had, buffers are allocated kind by kind instead
-    gdt = torch.bfloat16 if bf16 else torch.float32
     arena, placement = None, "separate allocations, kind by kind"
     if not args.no_arena:
         try:
             free, _ = torch.cuda.mem_get_info()
             arena = pier.HbmArena(free - (8 << 30) - (offload_slots * 2 * chunk if w.offload else 0), stream=stream)
-            placement = "probed arena of %d GiB, %d address classes" % (arena.buf.numel() >> 30, arena.n_classes)
+            placement = "probed arena of %d GiB, %d address classes, buffers placed by pier_placement_plan" % (
+                arena.buf.numel() >> 30, arena.n_classes)
         except (MemoryError, RuntimeError, pier.PierError) as e:
             print("bench.py: no arena (%s); allocating kind by kind" % e, file=sys.stderr)
     # workloads whose outer state lives in pinned host memory (the 7B configuration) take the
     # offload stream as their outer step; the PCIe time is then part of the step and `value`
     # is flagged as PCIe-inclusive in config
     host_outer = w.offload
-    # the 7B configuration keeps one gradient buffer for all replicas (each launch reads it whole,
-    # so the traffic is the same): nine of its 26 GiB buffers fit the three address classes, and
-    # only with a single gradient buffer do every replica's four streams lie in two classes
-    S = dev.PlacedState(w.numels, G, grad_dtype=gdt, arena=arena, outer="pinned" if host_outer else "device",
-                        shared_grad=host_outer)
-    P, M1, V, Gd, A, Mo = S.P, S.M1, S.V, S.Gd, S.A, S.Mo
-    with torch.cuda.stream(stream):
-        dev.init_params(P[0], w)
-        for g in range(1, G):
-            P[g].flat.copy_(P[0].flat)
-        for g in range(1 if host_outer else G):
-            Gd[g].fill_normal(seed=w.seed, stream=g, step=1, std=w.grad_std, hip_stream=stream)
-    stream.synchronize()
-    A.flat.copy_(P[0].flat)
+    S = State(w, arena, host_outer, stream)
+    ctx = S.ctx
     if host_outer:
-        Mo.flat.zero_()
-    torch.cuda.synchronize()
-
-    ctx = pier.pier_ctx_create(w.numels, G)
-    for g in range(G):
-        pier.pier_bind_replica(ctx, g, P[g].tensors, M1[g].tensors, V[g].tensors, Gd[g].tensors, bf16)
-    if host_outer:
-        pier.pier_bind_outer(ctx, pier.PIER_LOC_HOST_PINNED, A.flat, Mo.flat)
         ws = torch.empty(2 * chunk * offload_slots, dtype=torch.uint8, device="cuda")
         s_in, s_out = torch.cuda.Stream(), torch.cuda.Stream()
         pier.pier_ctx_set_offload_writeback(ctx, 0 if args.no_trailing else 1)
-    else:
-        pier.pier_bind_outer(ctx, pier.PIER_LOC_DEVICE, A.tensors, Mo.tensors)
 
     def outer_step():
         if host_outer:
@@ -193,15 +217,10 @@ def main():
         else:
             pier.pier_outer_step(ctx, outer_lr=lr_o, mu=mu, phase=pier.PIER_PHASE_PIER, stream=stream)
 
-    t_step = [0]
-
     def one_round(ev=None):
         if ev:
             ev[0].record(stream)
-        for _ in range(H):
-            t_step[0] += 1
-            for g in range(G):
-                pier.pier_inner_adamw(ctx, g, step=t_step[0], stream=stream, **hp)
+        S.inner_round(H, hp)
         if ev:
             ev[1].record(stream)
         outer_step()
@@ -220,6 +239,18 @@ def main():
 
     inner_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / (K * G * H)     # per AdamW launch
     outer_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / K               # per outer launch
+
+    def timed(fn, n):
+        """Average milliseconds of n calls of fn after one untimed call."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        e0.record(stream)
+        for _ in range(n):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
     # after the timed region: 20 more outer steps timed one by one (a round has only one)
     outer_each = []
     if not host_outer:
@@ -257,7 +288,7 @@ def main():
                          "256 A100 (Perlmutter), 1.2-1.9x on 64-128 GH200 (Vista); none for the optimizer step",
         "roofline": {"bound": "hbm", "kernel": "adamw_kernel (pier_inner_adamw)", "achieved": inner_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": inner_gbps / HBM_PEAK_GBPS,
-                     "traffic": traffic.get("adamw"), "traffic_unit": "GB per launch (rocprofv3 pmc)",
+                     "traffic": traffic.get("adamw"), "traffic_unit": TRAFFIC_NOTE,
                      "algorithmic_GB_per_launch": gbytes * N / 1e9,
                      "bytes_per_param": gbytes, "avg_launch_ms": inner_ms,
                      "launches_timed": K * G * H},
@@ -267,52 +298,51 @@ def main():
                                      "outer_kernel (pier_outer_step, Pier phase)",
                            "achieved": outer_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                            "frac": outer_gbps / HBM_PEAK_GBPS, "traffic": traffic.get("outer"),
-                           "traffic_unit": "GB per launch (rocprofv3 pmc)",
+                           "traffic_unit": TRAFFIC_NOTE,
                            "algorithmic_GB_per_launch": outer_bpe * N / 1e9,
                            "bytes_per_param": outer_bpe, "avg_launch_ms": outer_ms, "launches_timed": K},
     }
     if outer_each:
         out["roofline_outer"].update({"median_launch_ms_of_20_more": outer_each[len(outer_each) // 2],
                                       "min_max_launch_ms_of_20_more": [outer_each[0], outer_each[-1]]})
+    if not host_outer:
+        # the lazy-start synchronisation (Algorithm 1): theta_0, anchor, M read; anchor, M written
+        ms = timed(lambda: pier.pier_outer_step(ctx, outer_lr=lr_o, mu=mu, phase=pier.PIER_PHASE_WARMUP,
+                                                stream=stream), 20)
+        out["roofline_lazy_start"] = {"bound": "hbm", "kernel": "lazy_start_kernel (pier_outer_step, lazy-start phase)",
+                                      "achieved": 20 * N / ms / 1e6, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                      "frac": 20 * N / ms / 1e6 / HBM_PEAK_GBPS, "bytes_per_param": 20,
+                                      "avg_launch_ms": ms, "launches_timed": 20}
 
     if args.variants and not host_outer:
-        def timed(fn, n):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            fn()
-            e0.record(stream)
-            for _ in range(n):
-                fn()
-            e1.record(stream)
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / n
+        P = S.P
+        n_var = 20
 
         def all_replicas(call):
             def f():
-                t_step[0] += 1
+                S.t += 1
                 for g in range(G):
                     call(g)
             return f
 
         var = {}
-        ms = timed(all_replicas(lambda g: pier.pier_inner_adamw_clipped(ctx, g, step=t_step[0], max_norm=1.0,
-                                                                       stream=stream, **hp)), 3) / G
+        ms = timed(all_replicas(lambda g: pier.pier_inner_adamw_clipped(ctx, g, step=S.t, max_norm=1.0,
+                                                                       stream=stream, **hp)), n_var) / G
         var["adamw_clipped"] = {"ms": ms, "bytes_per_param": gbytes + (2 if bf16 else 4),
-                                "GBps": (gbytes + (2 if bf16 else 4)) * N / ms / 1e6}
-        ms = timed(lambda: pier.pier_outer_step(ctx, outer_lr=lr_o, mu=mu, phase=pier.PIER_PHASE_WARMUP,
-                                                stream=stream), 3)
-        var["outer_lazy_start"] = {"ms": ms, "bytes_per_param": 4 * G + 16, "GBps": (4 * G + 16) * N / ms / 1e6}
+                                "GBps": (gbytes + (2 if bf16 else 4)) * N / ms / 1e6, "launches": n_var * G}
         Wb = []
         for g in range(G):
             flat = arena.alloc(N, torch.bfloat16, P[g].cls)[0] if arena is not None else \
                 torch.empty(N, dtype=torch.bfloat16, device="cuda")
             Wb.append([flat[s0:s0 + n] for s0, n in zip(P[g].starts, w.numels)])
             pier.pier_bind_shadow(ctx, g, Wb[g])
-        ms = timed(all_replicas(lambda g: pier.pier_inner_adamw(ctx, g, step=t_step[0], stream=stream, **hp)), 3) / G
-        var["adamw_bf16_working_copy"] = {"ms": ms, "bytes_per_param": gbytes + 2, "GBps": (gbytes + 2) * N / ms / 1e6}
+        ms = timed(all_replicas(lambda g: pier.pier_inner_adamw(ctx, g, step=S.t, stream=stream, **hp)), n_var) / G
+        var["adamw_bf16_working_copy"] = {"ms": ms, "bytes_per_param": gbytes + 2, "GBps": (gbytes + 2) * N / ms / 1e6,
+                                          "launches": n_var * G}
         ms = timed(lambda: pier.pier_outer_step(ctx, outer_lr=lr_o, mu=mu, phase=pier.PIER_PHASE_PIER,
-                                                stream=stream), 3)
+                                                stream=stream), n_var)
         var["outer_bf16_working_copy"] = {"ms": ms, "bytes_per_param": outer_bpe + 2 * G,
-                                          "GBps": (outer_bpe + 2 * G) * N / ms / 1e6}
+                                          "GBps": (outer_bpe + 2 * G) * N / ms / 1e6, "launches": n_var}
         for g in range(G):
             pier.pier_bind_shadow(ctx, g, None)
         del Wb
@@ -323,7 +353,7 @@ def main():
         if not host_outer:
             hA, hM = dev.pinned_empty(N), dev.pinned_empty(N)      # exact size: pinned memory is scarce
             hM.zero_()
-            hA.copy_(A.flat)
+            hA.copy_(S.A.flat)
             pier.pier_bind_outer(ctx, pier.PIER_LOC_HOST_PINNED, hA, hM)
             ws = torch.empty(pier.pier_offload_workspace_bytes(ctx, chunk), dtype=torch.uint8, device="cuda")
             s_in, s_out = torch.cuda.Stream(), torch.cuda.Stream()
@@ -345,6 +375,67 @@ def main():
             "params_per_s": N / best.wall_ms * 1e3,
         }
 
+    pier.pier_ctx_destroy(ctx)
+    return out, arena is not None
+
+
+def run_plain(args, w, out):
+    """What a caller gets WITHOUT the probe and the plan: the same kernels on plain allocations
+    made kind by kind, a few launches."""
+    import torch
+    import paper_2511_17849_amd as pier
+    N, G = w.N, w.G
+    H = args.inner_steps or w.H
+    bf16 = w.grad_bf16
+    gbytes, outer_bpe = (26 if bf16 else 28), 8 * G + 16
+    hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay)
+    lr_o, mu = w.fixed_outer or (1.1, 0.9)
+    stream = torch.cuda.Stream()
+    S2 = State(w, None, False, stream)
+    Hp = min(H, 5)
+    S2.inner_round(1, hp)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev[0].record(stream)
+    S2.inner_round(Hp, hp)
+    ev[1].record(stream)
+    for _ in range(10):
+        pier.pier_outer_step(S2.ctx, outer_lr=lr_o, mu=mu, phase=pier.PIER_PHASE_PIER, stream=stream)
+    ev[2].record(stream)
+    torch.cuda.synchronize()
+    p_inner = ev[0].elapsed_time(ev[1]) / (Hp * G)
+    p_outer = ev[1].elapsed_time(ev[2]) / 10
+    out["roofline_plain_allocations"] = {
+        "what": "the same kernels on plain device allocations made kind by kind (no probe, no placement plan)",
+        "adamw": {"achieved": gbytes * N / p_inner / 1e6, "frac": gbytes * N / p_inner / 1e6 / HBM_PEAK_GBPS,
+                  "avg_launch_ms": p_inner, "launches_timed": Hp * G},
+        "outer": {"achieved": outer_bpe * N / p_outer / 1e6, "frac": outer_bpe * N / p_outer / 1e6 / HBM_PEAK_GBPS,
+                  "avg_launch_ms": p_outer, "launches_timed": 10},
+        "unit": "GB/s", "peak": HBM_PEAK_GBPS}
+    pier.pier_ctx_destroy(S2.ctx)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not "
+              "supported, run with --gpus 1" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    from pier_inputs import shapes
+    w = shapes.workloads()[args.workload]
+    baseline = None
+    if not args.no_cpu_baseline:
+        baseline = cpu_baseline(w)      # before any GPU call
+    import gc
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    out, had_arena = run_placed(args, w)
+    if had_arena and not w.offload and not args.no_plain:
+        gc.collect()                  # the arena held nearly all HBM: it is gone with run_placed's locals
+        torch.cuda.empty_cache()
+        run_plain(args, w, out)
     if baseline is not None:
         out["cpu_baseline"] = baseline
     print(json.dumps(out), flush=True)

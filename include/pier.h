@@ -264,6 +264,16 @@ pier_status pier_offload_stream(pier_ctx* ctx, const pier_outer_hp* hp, size_t c
 pier_status pier_hbm_probe(void* arena, size_t bytes, size_t granule_bytes, int32_t* class_out,
                            int n_granules, void* hip_stream);
 
+/* The classification step of the probe on its own (pure host arithmetic, touches no GPU):
+ * rates is a host array of n_granules x n_granules positive numbers, rates[a * n_granules + b]
+ * = the streaming rate of granules a and b together, in any unit; class_out as above.  Every
+ * threshold is a fraction of the best rate in the table: a pairing counts as "different
+ * classes" when it is within 3.3 % of the best rate; the arena counts as several classes
+ * only if at least 15 % of a sweep of granules are that fast against BOTH of granules 0 and
+ * 1 and the next slower sample lies at least 2 % of the best rate below them.  pier_hbm_probe
+ * is this routine fed with rates it measures on demand (a few hundred of the n^2 pairs). */
+pier_status pier_hbm_classify(const double* rates, int n_granules, int32_t* class_out);
+
 /* The placement that goes with the probe (again no operation of the paper; host
  * arithmetic only, touches no GPU).  Measured on MI355X: a launch streams fastest when
  * its buffers lie in exactly two classes, half in each.  For a model with n_replicas

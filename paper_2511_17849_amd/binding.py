@@ -97,6 +97,7 @@ def _load():
         "pier_offload_stream": (i32, [vp, ctypes.POINTER(OuterHP), ctypes.c_size_t, vp, ctypes.c_size_t,
                                       vp, vp, vp, ctypes.POINTER(OffloadStats)]),
         "pier_hbm_probe": (i32, [vp, ctypes.c_size_t, ctypes.c_size_t, ctypes.POINTER(ctypes.c_int32), i32, vp]),
+        "pier_hbm_classify": (i32, [ctypes.POINTER(ctypes.c_double), i32, ctypes.POINTER(ctypes.c_int32)]),
         "pier_mu_schedule": (f32, [i64, i64]),
         "pier_outer_lr_schedule": (f32, [i64, i64]),
         "pier_outer_schedule": (i32, [i64, i64, ctypes.POINTER(OuterHP)]),
@@ -305,6 +306,16 @@ def pier_hbm_probe(arena, granule_bytes, stream=None):
     n = int(nbytes // granule_bytes)
     out = (ctypes.c_int32 * max(n, 1))()
     _check(_load().pier_hbm_probe(arena.data_ptr() or None, nbytes, int(granule_bytes), out, n, _stream(stream)))
+    return list(out[:n])
+
+
+def pier_hbm_classify(rates):
+    """Class id of every granule from a full table of pair rates (n x n nested lists or array)."""
+    rows = [list(map(float, row)) for row in rates]
+    n = len(rows)
+    flat = (ctypes.c_double * (n * n))(*[x for row in rows for x in row])
+    out = (ctypes.c_int32 * max(n, 1))()
+    _check(_load().pier_hbm_classify(flat, n, out))
     return list(out[:n])
 
 

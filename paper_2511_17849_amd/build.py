@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpier.so")
-SOURCES = ["pier_kernels.hip", "pier_api.hip"]
+SOURCES = ["pier_kernels.hip", "pier_api.hip", "pier_placement.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -42,19 +42,7 @@ def build_abi_client(verbose=False):
     return exe
 
 
-def build_stream_bench(verbose=False):
-    """The stand-alone HBM streaming reference (csrc/hbm_stream_bench.hip)."""
-    exe = os.path.join(HERE, "hbm_stream_bench")
-    cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
-           "-packed-fp32-ops", "-o", exe, os.path.join(CSRC, "hbm_stream_bench.hip")]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
-    return exe
-
-
 if __name__ == "__main__":
     print(build(verbose=True))
     print(build_abi_client(verbose=True))
-    print(build_stream_bench(verbose=True))
     sys.exit(0)

@@ -1,7 +1,7 @@
 // Host side of libpier: the C ABI declared in include/pier.h.  Owns only small
 // tables (chunk lists, per-tensor pointer lists, events); every model-sized buffer
 // belongs to the caller.
-#include "../../include/pier.h"
+#include "pier_host.h"
 #include "pier_internal.h"
 
 #include <algorithm>
@@ -18,6 +18,62 @@
 
 using namespace pier;
 
+namespace {
+thread_local std::string g_last_error = "";
+}
+
+namespace pier {
+
+pier_status fail(pier_status st, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return st;
+}
+
+// A pointer handed over as "device memory": must be non-null, aligned to its
+// element, and lie with its whole extent inside one allocation of the current GPU.
+pier_status check_device_range(const void* ptr, int64_t numel, size_t elem, int device,
+                               const char* what, int tensor)
+{
+    if (numel == 0) return PIER_OK;
+    if (!ptr) return fail(PIER_ERR_INVALID_ARG, "%s[%d] is NULL", what, tensor);
+    if (reinterpret_cast<uintptr_t>(ptr) % elem)
+        return fail(PIER_ERR_ALIGNMENT, "%s[%d] is not aligned to %zu bytes", what, tensor, elem);
+    hipPointerAttribute_t at;
+    hipError_t e = hipPointerGetAttributes(&at, ptr);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PIER_ERR_INVALID_ARG, "%s[%d] is not memory known to HIP (%s)", what, tensor,
+                    hipGetErrorString(e));
+    }
+    if (at.type != hipMemoryTypeDevice && at.type != hipMemoryTypeManaged)
+        return fail(PIER_ERR_INVALID_ARG, "%s[%d] is not device memory", what, tensor);
+    if (at.type == hipMemoryTypeDevice && at.device != device)
+        return fail(PIER_ERR_INVALID_ARG, "%s[%d] lives on device %d, context on %d", what, tensor,
+                    at.device, device);
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    e = hipMemGetAddressRange(&base, &size, const_cast<void*>(ptr));
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PIER_ERR_INVALID_ARG, "%s[%d]: cannot query its allocation (%s)", what, tensor,
+                    hipGetErrorString(e));
+    }
+    const char* b = static_cast<const char*>(base);
+    const char* q = static_cast<const char*>(ptr);
+    if (q < b || q + static_cast<size_t>(numel) * elem > b + size)
+        return fail(PIER_ERR_INVALID_ARG, "%s[%d]: %lld elements do not fit its allocation", what,
+                    tensor, static_cast<long long>(numel));
+    return PIER_OK;
+}
+
+}  // namespace pier
+
 // Scratch of the entry point that allocates nothing (pier_inner_adamw_clipped_static): the
 // norm pass's record (one ClipState, in the first 256 bytes) followed by its per-workgroup
 // partial sums.  One copy per GPU, alive until the process ends, shared by every call on
@@ -32,31 +88,10 @@ static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {
 
-thread_local std::string g_last_error = "";
-
-pier_status fail(pier_status st, const char* fmt, ...)
-{
-    char buf[512];
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(buf, sizeof buf, fmt, ap);
-    va_end(ap);
-    g_last_error = buf;
-    return st;
-}
-
 // Device address of `scratch` on each GPU this process has used the library on.
 constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
 void* g_scratch_ptr[kMaxDevices] = {};
-
-#define PIER_HIP(call)                                                                      \
-    do {                                                                                    \
-        hipError_t e_ = (call);                                                             \
-        if (e_ != hipSuccess)                                                               \
-            return fail(e_ == hipErrorOutOfMemory ? PIER_ERR_OOM : PIER_ERR_HIP, "%s: %s",  \
-                        #call, hipGetErrorString(e_));                                      \
-    } while (0)
 
 // Resolves (once per device, with that device current) where this GPU keeps its copy of
 // `scratch`.  Allocates nothing.
@@ -214,43 +249,6 @@ pier_status ensure_device(pier_ctx* c)
         return st;
     }
     c->device = dev;
-    return PIER_OK;
-}
-
-// A pointer handed over as "device memory": must be non-null, aligned to its
-// element, and lie with its whole extent inside one allocation of the current GPU.
-pier_status check_device_range(const void* ptr, int64_t numel, size_t elem, int device,
-                               const char* what, int tensor)
-{
-    if (numel == 0) return PIER_OK;
-    if (!ptr) return fail(PIER_ERR_INVALID_ARG, "%s[%d] is NULL", what, tensor);
-    if (reinterpret_cast<uintptr_t>(ptr) % elem)
-        return fail(PIER_ERR_ALIGNMENT, "%s[%d] is not aligned to %zu bytes", what, tensor, elem);
-    hipPointerAttribute_t at;
-    hipError_t e = hipPointerGetAttributes(&at, ptr);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        return fail(PIER_ERR_INVALID_ARG, "%s[%d] is not memory known to HIP (%s)", what, tensor,
-                    hipGetErrorString(e));
-    }
-    if (at.type != hipMemoryTypeDevice && at.type != hipMemoryTypeManaged)
-        return fail(PIER_ERR_INVALID_ARG, "%s[%d] is not device memory", what, tensor);
-    if (at.type == hipMemoryTypeDevice && at.device != device)
-        return fail(PIER_ERR_INVALID_ARG, "%s[%d] lives on device %d, context on %d", what, tensor,
-                    at.device, device);
-    hipDeviceptr_t base = nullptr;
-    size_t size = 0;
-    e = hipMemGetAddressRange(&base, &size, const_cast<void*>(ptr));
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        return fail(PIER_ERR_INVALID_ARG, "%s[%d]: cannot query its allocation (%s)", what, tensor,
-                    hipGetErrorString(e));
-    }
-    const char* b = static_cast<const char*>(base);
-    const char* q = static_cast<const char*>(ptr);
-    if (q < b || q + static_cast<size_t>(numel) * elem > b + size)
-        return fail(PIER_ERR_INVALID_ARG, "%s[%d]: %lld elements do not fit its allocation", what,
-                    tensor, static_cast<long long>(numel));
     return PIER_OK;
 }
 
@@ -868,174 +866,6 @@ pier_status pier_offload_stream(pier_ctx* c, const pier_outer_hp* hp, size_t chu
     const pier_status st = offload_validate(c, hp, chunk_bytes, workspace, workspace_bytes, &S);
     if (st != PIER_OK) return st;
     return offload_enqueue(c, hp, S, workspace, compute_stream, h2d_stream, d2h_stream, stats);
-}
-
-pier_status pier_hbm_probe(void* arena, size_t bytes, size_t granule_bytes, int32_t* class_out,
-                           int n_granules, void* hip_stream)
-{
-    if (!arena || !class_out) return fail(PIER_ERR_INVALID_ARG, "arena or class_out is NULL");
-    const size_t kMiB = 1u << 20;
-    if (granule_bytes < 512 * kMiB || granule_bytes % (2 * kMiB))
-        return fail(PIER_ERR_INVALID_ARG, "granule_bytes must be a multiple of 2 MiB, at least 512 MiB");
-    if (reinterpret_cast<uintptr_t>(arena) % 16) return fail(PIER_ERR_ALIGNMENT, "arena is not aligned to 16 bytes");
-    if (n_granules < 2 || n_granules > 4096 || static_cast<size_t>(n_granules) > bytes / granule_bytes)
-        return fail(PIER_ERR_INVALID_ARG, "n_granules = %d does not fit %zu bytes of %zu-byte granules (need 2..4096)",
-                    n_granules, bytes, granule_bytes);
-    int dev = -1;
-    PIER_HIP(hipGetDevice(&dev));
-    pier_status st = check_device_range(arena, static_cast<int64_t>(granule_bytes) * n_granules, 1, dev, "arena", 0);
-    if (st != PIER_OK) return st;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    PIER_HIP(hipEventCreate(&e0));
-    if (hipEventCreate(&e1) != hipSuccess) {
-        (void)hipEventDestroy(e0);
-        return fail(PIER_ERR_HIP, "hipEventCreate failed");
-    }
-    // probe up to 2 GiB of each granule: far more than the 256 MB memory-side cache, and
-    // long enough (> 1 ms per pass) that ramp-up and tail do not blur the two rate levels
-    const size_t probe_bytes = std::min<size_t>(granule_bytes, 2048 * kMiB);
-    const int64_t n4 = static_cast<int64_t>(probe_bytes / 16);
-    char* base = static_cast<char*>(arena);
-    auto granule = [&](int g) { return reinterpret_cast<float*>(base + static_cast<size_t>(g) * granule_bytes); };
-    hipError_t err = hipSuccess;
-    const bool verbose = std::getenv("PIER_PROBE_VERBOSE") != nullptr;
-    // streaming rate (TB/s) of one in-place pass over granules a and b, faster of two
-    auto measure = [&](int a, int b) -> double {
-        double bestr = 0.0;
-        if (err == hipSuccess) err = launch_probe(granule(a), granule(b), n4, s);   // warm
-        for (int r = 0; r < 2 && err == hipSuccess; ++r) {
-            err = hipEventRecord(e0, s);
-            if (err == hipSuccess) err = launch_probe(granule(a), granule(b), n4, s);
-            if (err == hipSuccess) err = hipEventRecord(e1, s);
-            if (err == hipSuccess) err = hipEventSynchronize(e1);
-            float ms = 0.f;
-            if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
-            if (err == hipSuccess && ms > 0.f) bestr = std::max(bestr, 4.0 * probe_bytes / (ms * 1e9));
-        }
-        if (verbose) fprintf(stderr, "[pier probe] %d x %d: %.3f TB/s\n", a, b, bestr);
-        return bestr;
-    };
-    // Two granules of one class stream at 5.4-6.3 TB/s together (it swings with their
-    // distance, and neighbouring distances swing in opposite directions), two of different
-    // classes at 6.4-6.6 TB/s.  A first sweep pairs granules 0 and 1 with granules across the
-    // arena: the level of the fast group is the best single rate seen; the arena lies in one
-    // class when no granule is fast against BOTH references (the slower of the two pairings
-    // tops out near 6.1 TB/s inside a class and at 6.4+ across classes).
-    double fast = 0.0, fast_both = 0.0;
-    const int stride = std::max(1, n_granules / 24);
-    for (int t = 2; t < n_granules; t += stride) {
-        const double r0 = measure(0, t), r1 = measure(1, t);
-        fast = std::max(fast, std::max(r0, r1));
-        fast_both = std::max(fast_both, std::min(r0, r1));
-    }
-    const bool one_class = fast_both < 6.3;
-    const double thr = 0.967 * fast;
-    std::vector<std::vector<int>> classes;
-    for (int t = 0; t < n_granules && err == hipSuccess; ++t) {
-        int pick = -1;
-        double lowest = 1e30;
-        if (one_class) {
-            pick = classes.empty() ? -1 : 0;
-            lowest = 0.0;
-        } else {
-            for (size_t c = 0; c < classes.size() && err == hipSuccess; ++c) {
-                // against the first and the latest member of the class; the slower pairing
-                // decides (a few same-class distances stream almost as fast as cross-class pairs)
-                const std::vector<int>& m = classes[c];
-                double r = measure(m.front(), t);
-                if (m.back() != m.front() && r >= thr) r = std::min(r, measure(m.back(), t));
-                if (r < lowest) { lowest = r; pick = static_cast<int>(c); }
-            }
-        }
-        if (pick >= 0 && (lowest < thr || classes.size() >= 8)) classes[pick].push_back(t);
-        else classes.push_back(std::vector<int>(1, t));
-    }
-    if (err == hipSuccess)
-        for (size_t c = 0; c < classes.size(); ++c)
-            for (int t : classes[c]) class_out[t] = static_cast<int32_t>(c);
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    if (err != hipSuccess) return fail(PIER_ERR_HIP, "placement probe: %s", hipGetErrorString(err));
-    return PIER_OK;
-}
-
-pier_status pier_placement_plan(int n_classes, const int64_t* room_in, int n_replicas, int shared_grad,
-                                int outer_on_device, pier_replica_placement* replicas,
-                                int32_t* anchor_class, int32_t* momentum_class)
-{
-    if (n_classes < 1 || n_classes > 64) return fail(PIER_ERR_INVALID_ARG, "n_classes = %d, need 1..64", n_classes);
-    if (!room_in || !replicas || !anchor_class || !momentum_class)
-        return fail(PIER_ERR_INVALID_ARG, "a pointer is NULL");
-    if (n_replicas < 1 || n_replicas > PIER_MAX_REPLICAS)
-        return fail(PIER_ERR_INVALID_ARG, "n_replicas = %d, need 1..%d", n_replicas, PIER_MAX_REPLICAS);
-    std::vector<int64_t> room(room_in, room_in + n_classes);
-    for (int c = 0; c < n_classes; ++c)
-        if (room[c] < 0) return fail(PIER_ERR_INVALID_ARG, "room[%d] is negative", c);
-    const int two = std::min(2, n_classes);
-
-    // takes `count` buffers from the first class of prefs[0..n_prefs) that holds them all, else
-    // from the class with most room; -1 if no class holds them
-    auto take = [&](const int* prefs, int n_prefs, int count) -> int {
-        for (int i = 0; i < n_prefs; ++i)
-            if (room[prefs[i]] >= count) {
-                room[prefs[i]] -= count;
-                return prefs[i];
-            }
-        int best = 0;
-        for (int c = 1; c < n_classes; ++c)
-            if (room[c] > room[best]) best = c;
-        if (room[best] < count) return -1;
-        room[best] -= count;
-        return best;
-    };
-    auto full = [&]() { return fail(PIER_ERR_OOM, "the model's buffers do not fit the room given"); };
-
-    std::vector<int> outer_load(n_classes, 0);
-    for (int g = 0; g < n_replicas; ++g) {
-        const int want[2] = {g % two, (g + 1) % two};
-        int c = take(want, two, 2);                 // theta_g and m_g together
-        if (c >= 0) {
-            replicas[g].theta = replicas[g].m = c;
-        } else {
-            if ((replicas[g].theta = take(want, two, 1)) < 0) return full();
-            if ((replicas[g].m = take(want, two, 1)) < 0) return full();
-        }
-        ++outer_load[replicas[g].theta];
-    }
-    *anchor_class = *momentum_class = -1;
-    if (outer_on_device) {
-        for (int32_t* out : {anchor_class, momentum_class}) {
-            int lo = 0;
-            for (int c = 1; c < two; ++c)
-                if (outer_load[c] < outer_load[lo]) lo = c;
-            const int want[2] = {lo, (lo + 1) % two};
-            if ((*out = take(want, two, 1)) < 0) return full();
-            ++outer_load[*out];
-        }
-    }
-    int shared = -1;
-    for (int g = 0; g < n_replicas; ++g) {
-        // away from theta_g's class: class 2 first, then the other one of classes 0 and 1
-        const int th = replicas[g].theta;
-        int want[2];
-        int n_want = 0;
-        if (n_classes >= 3 && th != 2) want[n_want++] = 2;
-        if (n_classes >= 2) want[n_want++] = th == 0 ? 1 : 0;
-        if (n_want == 0) want[n_want++] = 0;
-        const bool need_grad = !shared_grad || shared < 0;
-        int c = take(want, n_want, need_grad ? 2 : 1);   // v_g and grad_g together
-        if (c >= 0) {
-            replicas[g].v = c;
-            replicas[g].grad = need_grad ? c : shared;
-        } else {
-            if ((replicas[g].v = take(want, n_want, 1)) < 0) return full();
-            replicas[g].grad = shared;
-            if (need_grad && (replicas[g].grad = take(want, n_want, 1)) < 0) return full();
-        }
-        if (shared_grad && shared < 0) shared = replicas[g].grad;
-    }
-    return PIER_OK;
 }
 
 float pier_mu_schedule(int64_t t, int64_t T)

@@ -68,3 +68,59 @@ class HbmArena:
                     lo = s * self.granule
                     return self.buf[lo:lo + numel * esize].view(dtype), c
         raise MemoryError("HbmArena: no run of %d free granules left" % need)
+
+
+class ModelBuffers:
+    """The model-sized flat buffers of one context - theta, m, v and the gradient of every
+    replica, the anchor and the outer momentum - placed as pier_placement_plan says: every
+    launch streams buffers of exactly two address classes, half in each (theta_g and m_g in
+    class g mod 2, back to back; v_g and grad_g in class 2 while it has room, else in the class
+    theta_g is not in; anchor and M in classes 0 and 1).  Memory plumbing only: the buffers are
+    uninitialised flat tensors; a caller cuts its tensor list out of each (tensors back to back).
+
+      arena            an HbmArena, or None for plain allocations made kind by kind
+      outer_on_device  False: the anchor and M live elsewhere (pinned host memory); the
+                       attributes ``anchor`` and ``momentum`` are then None
+      shared_grad      one gradient buffer for all replicas
+
+    ``classes`` gives the address class of every buffer (None without an arena)."""
+
+    def __init__(self, numel, n_replicas, grad_dtype=torch.float32, arena=None, outer_on_device=True,
+                 shared_grad=False, device="cuda"):
+        n = max(int(numel), 1)
+        G = int(n_replicas)
+        self.classes = {"theta": [None] * G, "m": [None] * G, "v": [None] * G, "grad": [None] * G,
+                        "anchor": None, "momentum": None}
+
+        def make(dtype, cls):
+            if arena is None:
+                return torch.empty(n, dtype=dtype, device=device), None
+            return arena.alloc(n, dtype, cls)
+
+        if arena is not None:
+            plan, ca, cm = _b.pier_placement_plan(arena.room(n), G, shared_grad, outer_on_device)
+        else:
+            plan, ca, cm = [dict(theta=None, m=None, v=None, grad=None)] * G, None, None
+        self.theta, self.m, self.v, self.grad = [], [], [], []
+        # allocation follows the order the plan was made in, so that buffers streamed together
+        # also end up next to each other inside their class
+        for g in range(G):
+            t, self.classes["theta"][g] = make(torch.float32, plan[g]["theta"])
+            m, self.classes["m"][g] = make(torch.float32, plan[g]["m"])
+            self.theta.append(t)
+            self.m.append(m)
+        self.anchor = self.momentum = None
+        if outer_on_device:
+            self.anchor, self.classes["anchor"] = make(torch.float32, ca)
+            self.momentum, self.classes["momentum"] = make(torch.float32, cm)
+        shared = None
+        for g in range(G):
+            v, self.classes["v"][g] = make(torch.float32, plan[g]["v"])
+            self.v.append(v)
+            if shared_grad and shared is not None:
+                self.grad.append(shared[0])
+                self.classes["grad"][g] = shared[1]
+            else:
+                shared = make(grad_dtype, plan[g]["grad"])
+                self.grad.append(shared[0])
+                self.classes["grad"][g] = shared[1]

@@ -160,10 +160,19 @@ class Run:
         if arena is not None:
             # carved out of a probed arena, placed by address class
             assert pad == 0
-            S = dev.PlacedState(numels, G, grad_dtype=gdt, arena=arena,
-                                outer="pinned" if offload else "device", shared_grad=shared_grad)
-            self.P, self.M1, self.V, self.Gd, self.A, self.Mo = S.P, S.M1, S.V, S.Gd, S.A, S.Mo
-            self.Mo.flat.zero_()
+            B = pier.ModelBuffers(sum(numels), G, grad_dtype=gdt, arena=arena, outer_on_device=not offload,
+                                  shared_grad=shared_grad)
+            wrap = lambda ts, cs: [dev.FlatList.wrap(t, numels, c) for t, c in zip(ts, cs)]
+            self.P, self.M1 = wrap(B.theta, B.classes["theta"]), wrap(B.m, B.classes["m"])
+            self.V, self.Gd = wrap(B.v, B.classes["v"]), wrap(B.grad, B.classes["grad"])
+            if offload:
+                self.A = dev.FlatList(numels, pinned=True)
+                self.Mo = dev.FlatList(numels, pinned=True)
+            else:
+                self.A = dev.FlatList.wrap(B.anchor, numels, B.classes["anchor"])
+                self.Mo = dev.FlatList.wrap(B.momentum, numels, B.classes["momentum"])
+            for fl in self.M1 + self.V + [self.Mo]:
+                fl.flat.zero_()
         else:
             self.P = [dev.FlatList(numels, pad=pad) for _ in range(G)]
             self.M1 = [dev.FlatList(numels, pad=pad) for _ in range(G)]

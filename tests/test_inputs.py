@@ -48,3 +48,14 @@ def test_workload_sizes():
     assert [len(w[k].tensors) for k in ("tiny", "gpt2_small", "gpt2_medium", "gpt2_xl", "gpt_7b")] == \
         [28, 148, 292, 580, 388]
     assert all(n % 4 == 0 for k in w for n in w[k].numels)
+
+
+def test_input_package_does_not_import_the_product_or_the_oracle():
+    """pier_inputs serves both sides, so it may lean on neither."""
+    import os
+    root = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "pier_inputs")
+    for dirpath, _, files in os.walk(root):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "paper_2511_17849_amd" not in text and "oracle" not in text.lower(), f
