@@ -375,6 +375,22 @@ def run_placed(args, w):
             "params_per_s": N / best.wall_ms * 1e3,
         }
 
+    if not host_outer and G >= 3:
+        # What the machine gives a PLAIN copy and a plain fill of model-sized buffers, by the array
+        # library's own kernels, in the same placement: the yardstick for mixed read/write streaming
+        # (the state is no longer needed, so the replicas serve as scratch).  theta_0 and theta_2 share
+        # an address class, theta_1 lies in the other one.
+        ref = {}
+        for name, fn, nbytes in (
+                ("copy_across_classes", lambda: S.P[1].flat.copy_(S.P[0].flat), 8 * N),
+                ("copy_within_a_class", lambda: S.P[2].flat.copy_(S.P[0].flat), 8 * N),
+                ("fill", lambda: S.P[1].flat.zero_(), 4 * N)):
+            with torch.cuda.stream(stream):
+                ms = timed(fn, 20)
+            ref[name] = {"GBps": nbytes / ms / 1e6, "frac": nbytes / ms / 1e6 / HBM_PEAK_GBPS, "ms": ms}
+        ref["what"] = ("torch copy_ / zero_ of one %d-byte buffer, 20 launches each: what plain library kernels "
+                       "stream at on this GPU" % (4 * N))
+        out["hbm_reference"] = ref
     pier.pier_ctx_destroy(ctx)
     return out, arena is not None
 

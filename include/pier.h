@@ -103,7 +103,7 @@ pier_status pier_ctx_set_launch(pier_ctx* ctx, int64_t chunk_elems, int unroll, 
  * lds_bytes: LDS reserved per workgroup and left unused, which caps the workgroups a
  * compute unit holds at floor(160 KiB / lds_bytes) (0 = no cap; at most 65536),
  * -1 = each kernel's measured best (12 waves per compute unit for the AdamW step, 8
- * for the outer step).  Default: 0, -1.  May be called at any time between launches. */
+ * for the outer step, 20 for the lazy-start synchronisation).  Default: 0, -1.  May be called at any time between launches. */
 pier_status pier_ctx_set_occupancy(pier_ctx* ctx, int wg_threads, int lds_bytes);
 
 /* Optional: how many workgroups, hence partial sums, the gradient-norm pass of the clipped
