@@ -27,7 +27,7 @@ HBM_PEAK_GBPS = 8000.0        # MI355X published HBM3E peak
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the
 # same counters' reading of a plain copy kernel); summary in
 # profiles/kernels_gpt2_xl_hbm_traffic_pmc.md.  Only valid for the workload it was taken on.
-MEASURED_TRAFFIC_GB = {"gpt2_xl": {"adamw": 44.003, "outer": 125.005}}
+MEASURED_TRAFFIC_GB = {"gpt2_xl": {"adamw": 44.003, "outer": 125.006, "lazy_start": 31.543}}
 TRAFFIC_NOTE = ("GB per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script "
                 "(profiles/kernels_gpt2_xl_hbm_traffic_pmc.md); a constant, not measured by this run")
 
@@ -197,6 +197,7 @@ def run_placed(args, w):
             arena = pier.HbmArena(free - (8 << 30) - (offload_slots * 2 * chunk if w.offload else 0), stream=stream)
             placement = "probed arena of %d GiB, %d address classes, buffers placed by pier_placement_plan" % (
                 arena.buf.numel() >> 30, arena.n_classes)
+            print("bench.py: %s; class map %s" % (placement, "".join(str(c) for c in arena.classes)), file=sys.stderr)
         except (MemoryError, RuntimeError, pier.PierError) as e:
             print("bench.py: no arena (%s); allocating kind by kind" % e, file=sys.stderr)
     # workloads whose outer state lives in pinned host memory (the 7B configuration) take the
@@ -312,6 +313,8 @@ def run_placed(args, w):
         out["roofline_lazy_start"] = {"bound": "hbm", "kernel": "lazy_start_kernel (pier_outer_step, lazy-start phase)",
                                       "achieved": 20 * N / ms / 1e6, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                       "frac": 20 * N / ms / 1e6 / HBM_PEAK_GBPS, "bytes_per_param": 20,
+                                      "traffic": traffic.get("lazy_start"), "traffic_unit": TRAFFIC_NOTE,
+                                      "algorithmic_GB_per_launch": 20 * N / 1e9,
                                       "avg_launch_ms": ms, "launches_timed": 20}
 
     if args.variants and not host_outer:
@@ -331,20 +334,26 @@ def run_placed(args, w):
         var["adamw_clipped"] = {"ms": ms, "bytes_per_param": gbytes + (2 if bf16 else 4),
                                 "GBps": (gbytes + (2 if bf16 else 4)) * N / ms / 1e6, "launches": n_var * G}
         Wb = []
-        for g in range(G):
-            flat = arena.alloc(N, torch.bfloat16, P[g].cls)[0] if arena is not None else \
-                torch.empty(N, dtype=torch.bfloat16, device="cuda")
-            Wb.append([flat[s0:s0 + n] for s0, n in zip(P[g].starts, w.numels)])
+        try:
+            for g in range(G):
+                flat = arena.alloc(N, torch.bfloat16, P[g].cls)[0] if arena is not None else \
+                    torch.empty(N, dtype=torch.bfloat16, device="cuda")
+                Wb.append([flat[s0:s0 + n] for s0, n in zip(P[g].starts, w.numels)])
+        except (MemoryError, RuntimeError) as e:
+            print("bench.py: no room for the bf16 working copies (%s); those variants are skipped" % e, file=sys.stderr)
+            Wb = []
+        for g in range(len(Wb)):
             pier.pier_bind_shadow(ctx, g, Wb[g])
-        ms = timed(all_replicas(lambda g: pier.pier_inner_adamw(ctx, g, step=S.t, stream=stream, **hp)), n_var) / G
-        var["adamw_bf16_working_copy"] = {"ms": ms, "bytes_per_param": gbytes + 2, "GBps": (gbytes + 2) * N / ms / 1e6,
-                                          "launches": n_var * G}
-        ms = timed(lambda: pier.pier_outer_step(ctx, outer_lr=lr_o, mu=mu, phase=pier.PIER_PHASE_PIER,
-                                                stream=stream), n_var)
-        var["outer_bf16_working_copy"] = {"ms": ms, "bytes_per_param": outer_bpe + 2 * G,
-                                          "GBps": (outer_bpe + 2 * G) * N / ms / 1e6, "launches": n_var}
-        for g in range(G):
-            pier.pier_bind_shadow(ctx, g, None)
+        if Wb:
+            ms = timed(all_replicas(lambda g: pier.pier_inner_adamw(ctx, g, step=S.t, stream=stream, **hp)), n_var) / G
+            var["adamw_bf16_working_copy"] = {"ms": ms, "bytes_per_param": gbytes + 2, "GBps": (gbytes + 2) * N / ms / 1e6,
+                                              "launches": n_var * G}
+            ms = timed(lambda: pier.pier_outer_step(ctx, outer_lr=lr_o, mu=mu, phase=pier.PIER_PHASE_PIER,
+                                                    stream=stream), n_var)
+            var["outer_bf16_working_copy"] = {"ms": ms, "bytes_per_param": outer_bpe + 2 * G,
+                                              "GBps": (outer_bpe + 2 * G) * N / ms / 1e6, "launches": n_var}
+            for g in range(G):
+                pier.pier_bind_shadow(ctx, g, None)
         del Wb
         out["variants"] = var
 
