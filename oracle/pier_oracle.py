@@ -135,9 +135,12 @@ _default = None
 
 
 def default():
+    """The oracle every module-level function below uses: the library built from pier_oracle.c
+    with CFLAGS, or the one PIER_ORACLE_LIB names (another build of the same source, e.g. the
+    instrumented one tests/test_oracle_sanitized.py makes)."""
     global _default
     if _default is None:
-        _default = Oracle()
+        _default = Oracle(os.environ.get("PIER_ORACLE_LIB") or None)
     return _default
 
 

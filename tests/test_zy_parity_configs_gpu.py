@@ -26,6 +26,14 @@ pytestmark = pytest.mark.gpu
 WARMUP, PIER = 0, 1
 
 
+# Gradient norm of the clipped step at full size, device against oracle.  Both sum exact products
+# in double; the oracle adds up to 2.1e9 squares one after the other, the device folds a tree, so
+# the two differ by the oracle's accumulated rounding: observed 4e-12 (GPT-2 XL, fp32 gradients)
+# to 2e-11 (GPT-2 medium, bf16 gradients) relative.  The bar is a small multiple of that; what it
+# protects is the fp32 coefficient (asserted to one ulp) and, through it, bit-exact updates.
+NORM_RTOL = 1e-10
+
+
 def _log(msg):
     print("[pier-parity] " + msg, flush=True)
 
@@ -39,18 +47,30 @@ def _free():
         host_empty()
 
 
+# What Algorithm 2's momentum branch and the outer-rate schedule of section "Implementation"
+# give at the synchronisations the configurations place in the schedule, worked out by hand:
+# (T, t) -> (phase, mu, outer lr); on the ramp lr = (t - 0.1 T) / (0.1 T).
+BY_HAND = {
+    (1100, 50): (WARMUP, 0.9, 0.0), (1100, 100): (WARMUP, 0.9, 0.0),
+    (1100, 150): (PIER, 0.99, 40.0 / 110.0), (1100, 200): (PIER, 0.95, 90.0 / 110.0),
+    (1800, 100): (WARMUP, 0.9, 0.0), (1800, 200): (PIER, 0.99, 20.0 / 180.0), (1800, 300): (PIER, 0.95, 120.0 / 180.0),
+}
+
+
 def _scalars(t, T, fixed):
-    """Outer scalars of the synchronisation at iteration t: from the library's schedule
-    helper, cross-checked against the oracle's own schedule."""
+    """Outer scalars of the synchronisation at iteration t: from the library's schedule helper,
+    checked against the values worked out by hand from the paper and against the oracle's
+    (independently written) schedule."""
     import paper_2511_17849_amd as pier
     from oracle import pier_oracle as O
     if not T:
         lr, mu = fixed
         return PIER, mu, lr
     hp = pier.pier_outer_schedule(t, T)
-    ph, mu, lr = O.outer_scalars(t, T)
-    assert (hp.phase, hp.mu, hp.outer_lr) == (ph, mu, lr)
-    return ph, mu, lr
+    ph, mu, lr = BY_HAND[(T, t)]
+    assert hp.phase == ph and hp.mu == np.float32(mu) and abs(hp.outer_lr - lr) <= 1e-7, (t, T, hp.phase, hp.mu, hp.outer_lr)
+    assert (hp.phase, hp.mu, hp.outer_lr) == O.outer_scalars(t, T)
+    return hp.phase, hp.mu, hp.outer_lr
 
 
 def _arena():
@@ -220,7 +240,8 @@ def test_one_tensor_of_more_than_2_to_31_elements():
         r.inner_steps(1)
         r.inner_steps(1, clip=1.0)
         for norm_o, coef_o, norm_d, coef_d in r.clip_log:
-            assert abs(norm_d - norm_o) <= 0.5 * sum(numels) * 2.0 ** -53 * norm_o
+            _log("big tensor clip: norms differ by %.2e relative" % (abs(norm_d - norm_o) / norm_o))
+            assert abs(norm_d - norm_o) <= NORM_RTOL * norm_o
             assert abs(coef_d - coef_o) <= 6e-8 * coef_o and coef_o < 0.03
         r.outer(mu=0.9, lr=1.1, phase=PIER)
         rep = r.check("big tensor")
@@ -245,7 +266,8 @@ def test_config3_shapes_clipped_steps_with_bf16_working_copies():
     r = H_.Run(w.numels, w.G, grad_bf16=True, seed=w.seed, sample=idx, shadow=True)
     r.inner_steps(2, clip=1.0)
     for norm_o, coef_o, norm_d, coef_d in r.clip_log:
-        assert abs(norm_d - norm_o) <= 0.5 * w.N * 2.0 ** -53 * norm_o      # see the XL case (observed 2e-11)
+        _log("medium clip: norms differ by %.2e relative" % (abs(norm_d - norm_o) / norm_o))
+        assert abs(norm_d - norm_o) <= NORM_RTOL * norm_o
         assert abs(coef_d - coef_o) <= 6e-8 * coef_o and 0.04 < coef_o < 0.07
     r.outer(mu=0.9, lr=1.1, phase=PIER)
     rep = r.check("medium clipped + bf16 copies")
@@ -274,10 +296,8 @@ def test_config4_gpt2_xl_clipped_step():
     r.inner_steps(1, clip=1.0)
     for norm_o, coef_o, norm_d, coef_d in r.clip_log:
         _log("XL clip: oracle norm %.12f coef %.9g | device norm %.12f coef %.9g" % (norm_o, coef_o, norm_d, coef_d))
-        # the oracle adds 1.56e9 squares one after the other in double; recursive summation of N
-        # positive terms is within N * 2^-53 relative of the exact sum (half of that for its square
-        # root), and the device's tree-shaped fold is tighter still (observed difference: 4e-12)
-        assert abs(norm_d - norm_o) <= 0.5 * w.N * 2.0 ** -53 * norm_o
+        _log("XL clip: norms differ by %.2e relative" % (abs(norm_d - norm_o) / norm_o))
+        assert abs(norm_d - norm_o) <= NORM_RTOL * norm_o
         assert abs(coef_d - coef_o) <= 6e-8 * coef_o and coef_o < 0.03
     rep = r.check("XL clipped")
     _log("XL clipped: %s" % rep)
