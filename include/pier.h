@@ -33,7 +33,12 @@
  *    chunk lists, events) that live as long as the context.
  *  - Kernels and copies are enqueued on the caller's streams; calls do not
  *    synchronise unless stated.  hip_stream arguments are hipStream_t values passed
- *    as void* (NULL = the null stream).
+ *    as void* (NULL = the null stream).  Once a context's tensors are bound, the launch
+ *    calls (pier_inner_adamw, pier_inner_adamw_clipped[_static], pier_outer_step and a
+ *    resident pier_train_step) enqueue kernels and nothing else - no allocation, no
+ *    memset, no copy, no synchronisation - so a caller may record them into a HIP graph.
+ *    Scalars (step, learning rates, mu) travel as kernel arguments and are fixed in a
+ *    recorded graph.
  *  - All model-sized buffers are fp32, updated in place.  A model is a list of
  *    n_tensors separately allocated tensors; tensor i has numel[i] elements.  A
  *    pointer must be aligned to its element size; 16-byte aligned tensors take the

@@ -569,6 +569,58 @@ def test_train_step_that_is_refused_launches_nothing(offload):
     assert [(t, ph) for t, ph, _, _ in r.sync_log] == [(4, WARMUP)]
 
 
+def test_round_replays_from_a_hip_graph():
+    """Nothing on the path synchronises, allocates or clears memory once a context is bound, so a
+    caller can record a whole round - clipped inner steps through the entry point that allocates
+    nothing, plain inner steps, lazy-start and Pier outer steps - into a HIP graph and replay it.
+    Every replay (with eager work and synchronisations in between) must leave exactly what the
+    same calls leave when issued eagerly."""
+    import paper_2511_17849_amd as pier
+    H_ = _harness()
+    numels = [4096 * 3, 1025, 7, 0, 50_000]
+    G = 3
+    hp = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+
+    def make():
+        r = H_.Run(numels, G, seed=61, shadow=True)
+        for g in range(G):
+            r.Gd[g].fill_normal(seed=61, stream=g, step=1, std=1e-3)
+        torch.cuda.synchronize()
+        return r
+
+    def round_(r, stream):
+        for step in (1, 2):
+            for g in range(G):
+                pier.pier_inner_adamw_clipped_static(r.ctx, g, step=step, max_norm=0.05, stream=stream, **hp)
+        pier.pier_outer_step(r.ctx, outer_lr=0.0, mu=0.9, phase=WARMUP, stream=stream)
+        for g in range(G):
+            pier.pier_inner_adamw(r.ctx, g, step=3, stream=stream, **hp)
+        pier.pier_outer_step(r.ctx, outer_lr=0.8, mu=0.95, phase=PIER, stream=stream)
+
+    eager, graphed = make(), make()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        round_(graphed, side)                      # warm-up outside the capture (first launches load code)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            round_(graphed, side)
+    torch.cuda.synchronize()
+    round_(eager, torch.cuda.current_stream())     # the warm-up round
+    for replay in range(3):
+        graph.replay()
+        round_(eager, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        a, b = eager.device_state(), graphed.device_state()
+        for k in a:
+            assert np.array_equal(a[k], b[k]), (replay, k)
+        scratch_user = H_.Run([3000], 1, seed=62)  # eager work between replays, sharing the static scratch
+        scratch_user.Gd[0].fill_normal(seed=62, stream=0, step=1, std=1e-3)
+        pier.pier_inner_adamw_clipped_static(scratch_user.ctx, 0, step=1, max_norm=0.01, **hp)
+        torch.cuda.synchronize()
+    assert np.abs(a["Mo"]).max() > 0
+
+
 def test_plain_c_client_of_the_abi(tmp_path):
     """A client that uses nothing but the C ABI, hipMalloc'd tensors and HIP streams (no torch):
     inner steps, the resident outer step, then the host-offload outer step; every buffer it
