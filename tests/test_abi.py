@@ -103,6 +103,14 @@ def test_host_side_argument_errors():
             pier.pier_ctx_set_occupancy(ctx, **bad)
     pier.pier_ctx_set_occupancy(ctx, wg_threads=64, lds_bytes=13312)
     pier.pier_ctx_set_occupancy(ctx)                    # back to each kernel's own choice
+    for bad in (-1, (1 << 20) + 1):
+        with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
+            pier.pier_ctx_set_norm_fold(ctx, bad)
+    pier.pier_ctx_set_norm_fold(ctx, 4096)
+    pier.pier_ctx_set_norm_fold(ctx, 0)                 # the default again
+    with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):      # the static-scratch step needs a bound replica too
+        pier.pier_inner_adamw_clipped_static(ctx, 0, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0,
+                                             step=1, max_norm=1.0)
     with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):
         pier.pier_inner_adamw(ctx, 0, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, step=1)
     with pytest.raises(pier.PierError, match="PIER_ERR_STATE"):

@@ -348,8 +348,8 @@ def test_lazy_start_sync_returns_the_model_bit_for_bit(G):
 
 def test_outer_nesterov_two_rounds_by_hand():
     # a = 0, M = 0, lr = 0.7, mu = 0.9, one group, exactly representable deltas.
-    # round 1: delta1 = 0.5          M1 = 0.5      theta1 = 0.7 (0.9*0.5 + 0.5) = 0.665
-    # round 2: model moved by 0.25   M2 = 0.9*0.5 + 0.25 = 0.7
+    # first step:  delta1 = 0.5          M1 = 0.5      theta1 = 0.7 (0.9*0.5 + 0.5) = 0.665
+    # second step: model moved by 0.25   M2 = 0.9*0.5 + 0.25 = 0.7
     #          theta2 = 0.665 + 0.7 (0.9*0.7 + 0.25) = 0.665 + 0.616 = 1.281
     a, M = f32([0.0]), f32([0.0])
     th = f32([0.5])
