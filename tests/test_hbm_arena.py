@@ -218,3 +218,33 @@ def test_classify_argument_errors():
     with pytest.raises(pier.PierError, match="PIER_ERR_INVALID_ARG"):
         pier.pier_hbm_classify(np.ones((1, 1)))
     assert pier.pier_hbm_classify(np.ones((2, 2))) == [0, 0]
+
+
+def test_classify_replays_a_recorded_probe_of_an_mi355x():
+    """The rates a real probe run measured (tests/golden/probe_rates_mi355x.txt: the 465 pairs it asked
+    for, of 140 x 140) classify into the three contiguous classes of 96, 96 and 88 GiB that run reported;
+    pairs the probe never measured are absent from the table (zero), so this also pins which pairs the
+    classifier needs.  The same table in GB/s gives the same answer."""
+    import os
+    import numpy as np
+    import paper_2511_17849_amd as pier
+    path = os.path.join(os.path.dirname(__file__), "golden", "probe_rates_mi355x.txt")
+    n, want, pairs = None, None, []
+    for line in open(path):
+        if line.startswith("# classes "):
+            want = [int(c) for c in line.split()[2]]
+        elif line.startswith("granules "):
+            n = int(line.split()[1])
+        elif line[0].isdigit():
+            a, b, r = line.split()
+            pairs.append((int(a), int(b), float(r)))
+    assert n == 140 and len(want) == n and len(pairs) == 465
+    R = np.zeros((n, n))
+    for a, b, r in pairs:
+        R[a, b] = R[b, a] = r
+    same = [r for a, b, r in pairs if want[a] == want[b]]
+    cross = [r for a, b, r in pairs if want[a] != want[b]]
+    assert max(same) < min(cross)                         # the two levels of this machine do not overlap
+    assert pier.pier_hbm_classify(R) == want
+    assert pier.pier_hbm_classify(R * 1000.0) == want
+    assert [want.count(c) for c in (0, 1, 2)] == [48, 48, 44]
