@@ -248,3 +248,48 @@ def test_classify_replays_a_recorded_probe_of_an_mi355x():
     assert pier.pier_hbm_classify(R) == want
     assert pier.pier_hbm_classify(R * 1000.0) == want
     assert [want.count(c) for c in (0, 1, 2)] == [48, 48, 44]
+
+
+def test_classify_and_plan_hold_their_contracts_on_random_input():
+    """Whatever the table, classification returns dense class ids starting at 0 (at most 8 classes);
+    whatever the room, a plan either fits - no class holds more buffers than it had room for, every
+    buffer of the model is placed once - or is refused as PIER_ERR_OOM."""
+    import numpy as np
+    import paper_2511_17849_amd as pier
+    rng = np.random.default_rng(2024)
+    for _ in range(200):
+        n = int(rng.integers(2, 60))
+        R = rng.uniform(0.5, 7.0, (n, n))
+        R = (R + R.T) / 2
+        got = pier.pier_hbm_classify(R)
+        assert got[0] == 0 and sorted(set(got)) == list(range(max(got) + 1)) and max(got) < 8
+    for _ in range(300):
+        ncls = int(rng.integers(1, 5))
+        room = [int(x) for x in rng.integers(0, 14, ncls)]
+        G = int(rng.integers(1, 9))
+        shared, outer = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        need = 3 * G + (1 if shared else G) + (2 if outer else 0)
+        try:
+            reps, ca, cm = pier.pier_placement_plan(room, G, shared_grad=shared, outer_on_device=outer)
+        except pier.PierError as e:
+            assert "PIER_ERR_OOM" in str(e)
+            # a refusal may also come from a split that first-fit could not make, never from ample room
+            assert sum(room) < need + 2 * ncls, (room, G, shared, outer)
+            continue
+        used = [0] * ncls
+        for r in reps:
+            for k in ("theta", "m", "v"):
+                used[r[k]] += 1
+        grads = {reps[0]["grad"]} if shared else None
+        if shared:
+            assert all(r["grad"] == reps[0]["grad"] for r in reps)
+            used[reps[0]["grad"]] += 1
+        else:
+            for r in reps:
+                used[r["grad"]] += 1
+        if outer:
+            used[ca] += 1
+            used[cm] += 1
+        else:
+            assert (ca, cm) == (-1, -1)
+        assert sum(used) == need and all(u <= r for u, r in zip(used, room)), (room, used)

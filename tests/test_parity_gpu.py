@@ -621,6 +621,55 @@ def test_round_replays_from_a_hip_graph():
     assert np.abs(a["Mo"]).max() > 0
 
 
+def test_two_threads_drive_two_contexts_at_once():
+    """The threading rule of the ABI: different contexts may be used from different threads at the
+    same time (each on its own stream); one thread's failing call does not disturb the other's
+    error text.  Results equal those of the same work done alone."""
+    import threading
+    import paper_2511_17849_amd as pier
+    H_ = _harness()
+    numels = [200_000, 1025, 7, 0, 4096]
+    hp = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+
+    def make(seed):
+        r = H_.Run(numels, 2, seed=seed, stream=torch.cuda.Stream())
+        for g in range(2):
+            r.Gd[g].fill_normal(seed=seed, stream=g, step=1, std=1e-3)
+        torch.cuda.synchronize()
+        return r
+
+    def work(r, errors, rounds=40):
+        try:
+            for k in range(rounds):
+                for g in range(2):
+                    pier.pier_inner_adamw_clipped(r.ctx, g, step=k + 1, max_norm=0.05, stream=r.stream, **hp)
+                pier.pier_outer_step(r.ctx, outer_lr=0.7, mu=0.9, phase=PIER if k % 2 else WARMUP, stream=r.stream)
+                try:                                   # a failing call on this thread, with its own message
+                    pier.pier_inner_adamw(r.ctx, 5 + r.seed, step=1, stream=r.stream, **hp)
+                except pier.PierError as e:
+                    assert "replica = %d" % (5 + r.seed) in str(e), str(e)
+            r.stream.synchronize()
+        except Exception as e:                         # surfaced in the main thread below
+            errors.append(e)
+
+    alone = [make(71), make(72)]
+    errs = []
+    for r in alone:
+        work(r, errs)
+    together = [make(71), make(72)]
+    threads = [threading.Thread(target=work, args=(r, errs)) for r in together]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(60)
+    assert not errs, errs
+    torch.cuda.synchronize()
+    for a, b in zip(alone, together):
+        sa, sb = a.device_state(), b.device_state()
+        for k in sa:
+            assert np.array_equal(sa[k], sb[k]), k
+
+
 def test_plain_c_client_of_the_abi(tmp_path):
     """A client that uses nothing but the C ABI, hipMalloc'd tensors and HIP streams (no torch):
     inner steps, the resident outer step, then the host-offload outer step; every buffer it
