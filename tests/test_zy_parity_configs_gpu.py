@@ -137,7 +137,8 @@ def test_config2_gpt2_small_every_element():
     buffer: a lazy-start round of the full H = 50 inner steps and its synchronisation, then a
     Pier round (5 inner steps, mu 0.99) - 1.1e11 oracle element updates, spread over the host
     cores.  A second run of the same case in a different launch shape (four-wave workgroups,
-    4096-element chunks, no residency cap) must give the same whole buffers bit for bit."""
+    4096-element chunks, no residency cap) and a third through the host-offload stream must give
+    the same whole buffers bit for bit."""
     import pier_harness as H_
     from pier_inputs import shapes
     w = shapes.workloads()["gpt2_small"]
@@ -146,9 +147,14 @@ def test_config2_gpt2_small_every_element():
     r = H_.Run(w.numels, w.G, hp=hp, seed=w.seed, full_checks=True)
     other = H_.Run(w.numels, w.G, hp=hp, seed=w.seed, sample=np.arange(8, dtype=np.int64),
                    launch=dict(chunk_elems=4096, unroll=2, wg_threads=256, lds_bytes=0))
+    # and a third with the outer state in pinned host memory, streamed in pieces whose size divides
+    # neither the model nor its tensors (24 MiB + 4 KiB): 21 pieces
+    off = H_.Run(w.numels, w.G, hp=hp, seed=w.seed, sample=np.arange(8, dtype=np.int64), offload=True,
+                 chunk_bytes=(24 << 20) + 4096)
+    off.want_stats = False
     try:
         for k, (H, ph, mu, lr) in enumerate([(w.H, WARMUP, 0.9, 0.0), (5, PIER, 0.99, 40.0 / 110.0)]):
-            for run in (r, other):
+            for run in (r, other, off):
                 run.inner_steps(H, shared_stream=(ph == WARMUP))
                 run.outer(mu=mu, lr=lr, phase=ph)
             rep = r.check("config 2 dense, round %d" % k)
@@ -159,9 +165,13 @@ def test_config2_gpt2_small_every_element():
             for a, b in ((r.P[g], other.P[g]), (r.M1[g], other.M1[g]), (r.V[g], other.V[g])):
                 assert torch.equal(a.flat, b.flat)
         assert torch.equal(r.A.flat, other.A.flat) and torch.equal(r.Mo.flat, other.Mo.flat)
+        for g in range(w.G):
+            for a, b in ((r.P[g], off.P[g]), (r.M1[g], off.M1[g]), (r.V[g], off.V[g])):
+                assert torch.equal(a.flat, b.flat)
+        assert torch.equal(r.A.flat.cpu(), off.A.flat[:w.N]) and torch.equal(r.Mo.flat.cpu(), off.Mo.flat[:w.N])
         _log("config 2 dense whole-buffer checks: %s" % r.full_log)
     finally:
-        del r, other
+        del r, other, off
         _free()
 
 
