@@ -204,7 +204,19 @@ def run_placed(args, w):
     # offload stream as their outer step; the PCIe time is then part of the step and `value`
     # is flagged as PCIe-inclusive in config
     host_outer = w.offload
-    S = State(w, arena, host_outer, stream)
+    try:
+        S = State(w, arena, host_outer, stream)
+    except (MemoryError, pier.PierError) as e:
+        if arena is None:
+            raise
+        # the probed classes leave no room for this model's plan: run on plain allocations instead
+        print("bench.py: the placement plan does not fit the probed arena (%s); allocating kind by kind" % e,
+              file=sys.stderr)
+        arena, placement = None, "separate allocations, kind by kind (the plan did not fit the probed arena)"
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        S = State(w, None, host_outer, stream)
     ctx = S.ctx
     if host_outer:
         ws = torch.empty(2 * chunk * offload_slots, dtype=torch.uint8, device="cuda")
