@@ -80,12 +80,14 @@ def _compare(numels, seed, bf16, max_norm, step, stream):
         p, m, v = (host[k][i].numpy().copy() for k in range(3))
         g = host[3][i]
         g = np.ascontiguousarray(g.view(torch.int16).numpy().view(np.uint16)) if bf16 else g.numpy()
-        O.adamw(p, m, v, g, step=step, grad_scale=got[1], **HP)       # the device's coefficient: the step itself is exact
+        O.adamw(p, m, v, g, step=step, grad_scale=coef, **HP)         # the oracle's own coefficient
         for name, want, have in (("theta", p, a[0][i]), ("m", m, a[1][i]), ("v", v, a[2][i])):
             have = have.cpu().numpy()
             assert np.all(np.abs(have.astype(np.float64) - want) <= 1e-6 * np.maximum(1.0, np.abs(want))), name
-            assert np.array_equal(have, want), name
-        assert np.array_equal(O.to_bf16(p), a[4][i].cpu().view(torch.int16).numpy().view(np.uint16))
+            if np.float32(got[1]) == np.float32(coef):                # same fp32 coefficient: same bits
+                assert np.array_equal(have, want), name
+        if np.float32(got[1]) == np.float32(coef):
+            assert np.array_equal(O.to_bf16(p), a[4][i].cpu().view(torch.int16).numpy().view(np.uint16))
     return got
 
 
