@@ -80,6 +80,35 @@ MUTATIONS = [
     ("lazy start ends one step early", "return passed(t, T, k10pct) ? 1 : 0;", "return reached(t, T, k10pct) ? 1 : 0;"),
     ("warmup mu taken from the decay schedule", "if (*phase == 0) { *mu = 0.9f; *lr = 0.0f; }",
      "if (*phase == 0) { *mu = pier_oracle_mu(t, T); *lr = 0.0f; }"),
+    ("v bias-corrected with beta1's factor", "float vh = vn / bc2;", "float vh = vn / bc1;"),
+    ("om1 from beta2", "float om1 = 1.0f - beta1;", "float om1 = 1.0f - beta2;"),
+    ("om2 from beta1", "float om2 = 1.0f - beta2;", "float om2 = 1.0f - beta1;"),
+    ("bias correction one step early", "pow((double)beta2, (double)step)", "pow((double)beta2, (double)(step + 1))"),
+    ("decay not scaled by lr", "float u = mh / (sqrtf(vh) + eps) + wd * (*p);\n    *p = *p - lr * u;",
+     "float u = mh / (sqrtf(vh) + eps);\n    *p = *p - lr * u - wd * (*p);"),
+    ("clip coefficient inverted", "double coef = (double)max_norm / (sqrt(sumsq) + 1e-6);",
+     "double coef = (sqrt(sumsq) + 1e-6) / (double)max_norm;"),
+    ("clip: squares formed in float", "acc = acc + (double)g[i] * (double)g[i];", "acc = acc + (double)(g[i] * g[i]);"),
+    ("clip: accumulated in float", "acc = acc + (double)g[i] * (double)g[i];", "acc = (double)((float)acc + g[i] * g[i]);"),
+    ("outer: rate on the momentum term only", "a[i] + lr * (mu * Mn + d)", "a[i] + (lr * mu * Mn + d)"),
+    ("outer: mean over G-1", "float invG = 1.0f / (float)G;", "float invG = 1.0f / (float)(G > 1 ? G - 1 : 1);"),
+    ("outer: mu squared in the look-ahead", "lr * (mu * Mn + d)", "lr * (mu * mu * Mn + d)"),
+    ("outer: anchor moved by the plain difference", "float x = a[i] + lr * (mu * Mn + d);", "float x = a[i] + d;"),
+    ("lr: 80% breakpoint at 85%", "k80pct = {4, 5}", "k80pct = {17, 20}"),
+    ("lr: plateau 1.0 instead of 1.1", "if (reached(t, T, k20pct)) return 1.1f;", "if (reached(t, T, k20pct)) return 1.0f;"),
+    ("lr: final value 1.0 instead of 0.9", "if (reached(t, T, k80pct)) return 0.9f;", "if (reached(t, T, k80pct)) return 1.0f;"),
+    ("mu 0.999 instead of 0.99", "return 0.99f;", "return 0.999f;"),
+    ("mu: 20% typed as 1/4", "k20pct = {1, 5}", "k20pct = {1, 4}"),
+    ("mu: 10% typed as 1/8", "k10pct = {1, 10}", "k10pct = {1, 8}"),
+    ("inner lr: warmup one iteration late", "return (float)(hi * (double)t / W);", "return (float)(hi * (double)(t - 1) / W);"),
+    ("inner lr: lr_min reached half way", "double progress = ((double)t - W) / ((double)T - W);",
+     "double progress = 2.0 * ((double)t - W) / ((double)T - W); if (progress > 1.0) progress = 1.0;"),
+    ("bf16: rounds the magnitude up always", "out[i] = (uint16_t)((b + 0x7FFFu + lsb) >> 16);", "out[i] = (uint16_t)((b + 0xFFFFu) >> 16);"),
+    ("bf16 gradient: low half used", "uint32_t bits = (uint32_t)g[i] << 16;\n        float gf;\n        memcpy(&gf, &bits, sizeof gf);\n        adamw_one",
+     "uint32_t bits = (uint32_t)g[i];\n        float gf;\n        memcpy(&gf, &bits, sizeof gf);\n        adamw_one"),
+    ("lazy start: momentum from the old model only", "float delta = model[i] - a[i];", "float delta = -a[i];"),
+    ("warmup scalars: rate not zero", "if (*phase == 0) { *mu = 0.9f; *lr = 0.0f; }",
+     "if (*phase == 0) { *mu = 0.9f; *lr = pier_oracle_outer_lr(t, T) + 0.5f; }"),
 ]
 
 
