@@ -163,6 +163,60 @@ def test_adamw_matches_float64_recurrence():
     np.testing.assert_allclose(v, v64, rtol=5e-6, atol=1e-16)
 
 
+@pytest.mark.parametrize("case", range(12))
+def test_rounds_with_random_scalars_stay_near_the_float64_evaluation(case):
+    """Random hyper-parameters, group counts and phase sequences: the fp32 oracle stays within the
+    parity bar of the same rules carried in float64 (numpy, whole arrays at once).  A breadth check on
+    top of the pins above: nothing in the oracle is tuned to one set of scalars."""
+    rng = np.random.default_rng(500 + case)
+    n = 2000
+    G = int(rng.choice([1, 2, 3, 5, 8]))
+    hp = dict(lr=float(rng.choice([1e-4, 3e-4, 1e-3])), beta1=float(rng.choice([0.8, 0.9])),
+              beta2=float(rng.choice([0.95, 0.99, 0.999])), eps=float(rng.choice([1e-8, 1e-6])),
+              weight_decay=float(rng.choice([0.0, 0.01, 0.1])), grad_scale=float(rng.choice([1.0, 0.25, 0.6]))
+              )
+    c = {k: float(np.float32(v)) for k, v in hp.items()}
+    th0 = rng.normal(0, 0.02, n).astype(np.float32)
+    P = [th0.copy() for _ in range(G)]
+    M1 = [np.zeros(n, np.float32) for _ in range(G)]
+    V = [np.zeros(n, np.float32) for _ in range(G)]
+    a, Mo = th0.copy(), np.zeros(n, np.float32)
+    P64 = [th0.astype(np.float64) for _ in range(G)]
+    M64 = [np.zeros(n) for _ in range(G)]
+    V64 = [np.zeros(n) for _ in range(G)]
+    a64, Mo64 = th0.astype(np.float64), np.zeros(n)
+    t = 0
+    for rnd in range(4):
+        lazy = rnd < int(rng.integers(0, 3))
+        for _ in range(int(rng.integers(1, 6))):
+            t += 1
+            shared = rng.normal(0, 1e-3, n).astype(np.float32)
+            for g in range(G):
+                gr = shared if lazy else rng.normal(0, 1e-3, n).astype(np.float32)
+                O.adamw(P[g], M1[g], V[g], gr, step=t, **hp)
+                g64 = gr.astype(np.float64) * c["grad_scale"]
+                M64[g] = c["beta1"] * M64[g] + (1 - c["beta1"]) * g64
+                V64[g] = c["beta2"] * V64[g] + (1 - c["beta2"]) * g64 * g64
+                P64[g] = P64[g] - c["lr"] * (M64[g] / (1 - c["beta1"] ** t) / (np.sqrt(V64[g] / (1 - c["beta2"] ** t)) + c["eps"])
+                                             + c["weight_decay"] * P64[g])
+        mu, lr_o = float(np.float32(rng.choice([0.9, 0.95, 0.99]))), float(np.float32(rng.choice([0.3, 0.7, 1.1])))
+        O.outer(P, a, Mo, mu=mu, lr=lr_o, phase=O.WARMUP if lazy else O.PIER)
+        if lazy:
+            Mo64 = mu * Mo64 + (P64[0] - a64)
+            a64 = P64[0].copy()
+        else:
+            d = np.mean(np.stack(P64), axis=0) - a64
+            Mo64 = mu * Mo64 + d
+            a64 = a64 + lr_o * (mu * Mo64 + d)
+            P64 = [a64.copy() for _ in range(G)]
+        assert np.all(np.abs(a - a64) <= tol(a64)), (case, rnd)
+        np.testing.assert_allclose(Mo, Mo64, rtol=1e-4, atol=2e-8)      # a difference of models: a few ulp of theta
+        for g in range(G):
+            assert np.all(np.abs(P[g] - P64[g]) <= tol(P64[g])), (case, rnd, g)
+            np.testing.assert_allclose(M1[g], M64[g], rtol=1e-5, atol=1e-10)
+            np.testing.assert_allclose(V[g], V64[g], rtol=1e-5, atol=1e-16)
+
+
 def test_adamw_bf16_gradients_widen_exactly():
     from pier_inputs import generator as gen
     rng = np.random.default_rng(4)
