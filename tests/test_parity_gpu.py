@@ -117,7 +117,7 @@ def test_grad_scale_and_other_hyperparameters():
     assert rep["bit_exact"], rep
 
 
-@pytest.mark.parametrize("case", range(24))
+@pytest.mark.parametrize("case", range(64))
 def test_randomised_small_cases(case):
     """Seeded random tensor lists (odd sizes, empty tensors, sizes around chunk multiples), group
     counts 1..16, launch shapes, gradient dtype, padding, phase sequence and scalars."""
