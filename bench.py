@@ -411,6 +411,13 @@ def run_placed(args, w):
             ref[name] = {"GBps": nbytes / ms / 1e6, "frac": nbytes / ms / 1e6 / HBM_PEAK_GBPS, "ms": ms}
         ref["what"] = ("torch copy_ / zero_ of one %d-byte buffer, 20 launches each: what plain library kernels "
                        "stream at on this GPU" % (4 * N))
+        if arena is not None:
+            # and the best the placement probe saw at set-up: two 2 GiB buffers streamed in place with
+            # trivial arithmetic (read both, add, write both) - the two kernels' access pattern at its simplest
+            ref["probe_best_two_buffer_in_place"] = {"GBps": 1e3 * arena.probe["best_rate"],
+                                                     "frac": 1e3 * arena.probe["best_rate"] / HBM_PEAK_GBPS,
+                                                     "cross_class_threshold_GBps": 1e3 * arena.probe["threshold"],
+                                                     "pairs_timed": arena.probe["n_pairs"]}
         out["hbm_reference"] = ref
     pier.pier_ctx_destroy(ctx)
     return out, arena is not None

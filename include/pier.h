@@ -279,6 +279,15 @@ pier_status pier_hbm_probe(void* arena, size_t bytes, size_t granule_bytes, int3
  * is this routine fed with rates it measures on demand (a few hundred of the n^2 pairs). */
 pier_status pier_hbm_classify(const double* rates, int n_granules, int32_t* class_out);
 
+/* What the calling thread's most recent pier_hbm_probe (or pier_hbm_classify) saw: the
+ * fastest pairing (for the probe: TB/s of a two-buffer in-place streaming pass with
+ * trivial arithmetic, i.e. what this GPU gives the access pattern of the two optimizer
+ * kernels at best), the level a pairing had to reach to count as "different classes"
+ * (0 when the arena is one class), the number of classes and of pairings asked for.  Any
+ * output may be NULL.  PIER_ERR_STATE before the thread's first probe. */
+pier_status pier_hbm_probe_summary(double* best_rate, double* threshold, int32_t* n_classes,
+                                   int32_t* n_pairs);
+
 /* The placement that goes with the probe (again no operation of the paper; host
  * arithmetic only, touches no GPU).  Measured on MI355X: a launch streams fastest when
  * its buffers lie in exactly two classes, half in each.  For a model with n_replicas

@@ -97,6 +97,8 @@ def _load():
         "pier_offload_stream": (i32, [vp, ctypes.POINTER(OuterHP), ctypes.c_size_t, vp, ctypes.c_size_t,
                                       vp, vp, vp, ctypes.POINTER(OffloadStats)]),
         "pier_hbm_probe": (i32, [vp, ctypes.c_size_t, ctypes.c_size_t, ctypes.POINTER(ctypes.c_int32), i32, vp]),
+        "pier_hbm_probe_summary": (i32, [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                         ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]),
         "pier_hbm_classify": (i32, [ctypes.POINTER(ctypes.c_double), i32, ctypes.POINTER(ctypes.c_int32)]),
         "pier_mu_schedule": (f32, [i64, i64]),
         "pier_outer_lr_schedule": (f32, [i64, i64]),
@@ -307,6 +309,14 @@ def pier_hbm_probe(arena, granule_bytes, stream=None):
     out = (ctypes.c_int32 * max(n, 1))()
     _check(_load().pier_hbm_probe(arena.data_ptr() or None, nbytes, int(granule_bytes), out, n, _stream(stream)))
     return list(out[:n])
+
+
+def pier_hbm_probe_summary():
+    """dict(best_rate, threshold, n_classes, n_pairs) of this thread's latest probe / classification."""
+    b, t = ctypes.c_double(), ctypes.c_double()
+    c, n = ctypes.c_int32(), ctypes.c_int32()
+    _check(_load().pier_hbm_probe_summary(ctypes.byref(b), ctypes.byref(t), ctypes.byref(c), ctypes.byref(n)))
+    return dict(best_rate=b.value, threshold=t.value, n_classes=c.value, n_pairs=n.value)
 
 
 def pier_hbm_classify(rates):

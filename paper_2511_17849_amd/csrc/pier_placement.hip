@@ -29,14 +29,26 @@ constexpr double kGap = 0.02;        // the two levels of the sweep must be at l
 constexpr double kBandShare = 0.15;  // ... and the top level must hold at least this share of the sweep (and two samples)
 constexpr int kMaxClasses = 8;
 
+// What the calling thread's most recent classification saw (pier_hbm_probe_summary).
+struct ProbeSummary {
+    double best = 0.0;        // fastest pairing
+    double threshold = 0.0;   // level a pairing must reach to count as cross-class
+    int n_classes = 0;
+    int n_pairs = 0;          // pairings asked for
+};
+thread_local ProbeSummary g_summary;
+
 // rate(a, b): streaming rate of granules a and b together (any unit, > 0), measured or
 // looked up; n granules.  Returns false when rate() reported a failure (a value <= 0).
 bool classify_granules(int n, const std::function<double(int, int)>& rate, int32_t* class_out)
 {
+    g_summary = ProbeSummary();
     bool ok = true;
     auto r = [&](int a, int b) {
         const double x = rate(a, b);
         if (!(x > 0.0)) ok = false;
+        ++g_summary.n_pairs;
+        if (x > g_summary.best) g_summary.best = x;
         return x;
     };
     // First sweep: granules 0 and 1 (adjacent, so of one class unless a class ends between them)
@@ -109,6 +121,8 @@ bool classify_granules(int n, const std::function<double(int, int)>& rate, int32
     if (!ok) return false;
     for (size_t c = 0; c < classes.size(); ++c)
         for (int t : classes[c]) class_out[t] = static_cast<int32_t>(c);
+    g_summary.threshold = one_class ? 0.0 : thr;
+    g_summary.n_classes = static_cast<int>(classes.size());
     return true;
 }
 
@@ -124,6 +138,17 @@ pier_status pier_hbm_classify(const double* rates, int n_granules, int32_t* clas
     const size_t n = static_cast<size_t>(n_granules);
     const bool ok = classify_granules(n_granules, [&](int a, int b) { return rates[a * n + b]; }, class_out);
     if (!ok) return fail(PIER_ERR_INVALID_ARG, "the rate table has an entry that is not a positive number");
+    return PIER_OK;
+}
+
+pier_status pier_hbm_probe_summary(double* best_rate, double* threshold, int32_t* n_classes, int32_t* n_pairs)
+{
+    if (g_summary.n_pairs == 0 && g_summary.n_classes == 0)
+        return fail(PIER_ERR_STATE, "this thread has not run pier_hbm_probe or pier_hbm_classify");
+    if (best_rate) *best_rate = g_summary.best;
+    if (threshold) *threshold = g_summary.threshold;
+    if (n_classes) *n_classes = g_summary.n_classes;
+    if (n_pairs) *n_pairs = g_summary.n_pairs;
     return PIER_OK;
 }
 

@@ -18,6 +18,7 @@ class HbmArena:
         n = int(nbytes + self.granule - 1) // self.granule
         self.buf = torch.empty(n * self.granule, dtype=torch.uint8, device=device)
         self.classes = _b.pier_hbm_probe(self.buf, self.granule, stream)
+        self.probe = _b.pier_hbm_probe_summary()      # best pair rate (TB/s), threshold, classes, pairs
         self.used = [False] * n
         self.n_classes = max(self.classes) + 1
 

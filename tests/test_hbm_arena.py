@@ -246,6 +246,9 @@ def test_classify_replays_a_recorded_probe_of_an_mi355x():
     cross = [r for a, b, r in pairs if want[a] != want[b]]
     assert max(same) < min(cross)                         # the two levels of this machine do not overlap
     assert pier.pier_hbm_classify(R) == want
+    summary = pier.pier_hbm_probe_summary()
+    assert summary["n_classes"] == 3 and summary["n_pairs"] == 465 and summary["best_rate"] == max(cross)
+    assert max(same) < summary["threshold"] < min(cross)
     assert pier.pier_hbm_classify(R * 1000.0) == want
     assert [want.count(c) for c in (0, 1, 2)] == [48, 48, 44]
 
